@@ -1,0 +1,267 @@
+"""ctypes/numpy front end of the CPU oracle (``fae_oracle.c``).
+
+TEST INFRASTRUCTURE ONLY: imported by ``tests/``, ``__graft_entry__.smoke()`` and
+the ``cpu_baseline`` leg of ``bench.py``; never by the product package.  It
+marshals numpy arrays into the C functions and loops over tables; all arithmetic
+lives in the C file.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from typing import List, Optional, Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "fae_oracle.c")
+_LIB = os.path.join(_HERE, "libfae_oracle.so")
+
+OK, EINVAL, ERANGE, ENOSPC = 0, -1, -2, -3
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (no fast-math, no FMA contraction)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-ffp-contract=off",
+               "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"]
+        subprocess.check_call(cmd)
+    return _LIB
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        _lib = C.CDLL(build())
+        _lib.orc_cutoff_eq1.restype = C.c_double
+        _lib.orc_cutoff_eq1.argtypes = [C.c_double] * 3
+        _lib.orc_cutoff_int.restype = C.c_uint32
+        _lib.orc_cutoff_int.argtypes = [C.c_double]
+        _lib.orc_count_hot.restype = C.c_int64
+        _lib.orc_classify.restype = C.c_int64
+        _lib.orc_runs.restype = C.c_int64
+        _lib.orc_w0.restype = C.c_float
+        _lib.orc_w0.argtypes = [C.c_uint64, C.c_int32, C.c_int64, C.c_int32, C.c_int32]
+    return _lib
+
+
+def _p(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+def _arr(a, dtype) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=dtype)
+
+
+def _ptr_array(arrs: Sequence[Optional[np.ndarray]]):
+    out = (C.c_void_p * len(arrs))()
+    for i, a in enumerate(arrs):
+        out[i] = None if a is None else a.ctypes.data
+    return out
+
+
+class OracleError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        super().__init__(f"oracle {where}: error {code}")
+        self.code = code
+
+
+def _check(rc: int, where: str):
+    if rc != OK:
+        raise OracleError(rc, where)
+
+
+# -- profiling ---------------------------------------------------------------------
+def histogram(n_rows: int, idx: np.ndarray, cnt: Optional[np.ndarray] = None) -> np.ndarray:
+    idx = _arr(idx, np.int32)
+    if cnt is None:
+        cnt = np.zeros(n_rows, dtype=np.uint32)
+    assert cnt.dtype == np.uint32 and cnt.size == n_rows and cnt.flags.c_contiguous
+    _check(lib().orc_histogram(C.c_int64(n_rows), _p(idx), C.c_int64(idx.size), _p(cnt)), "histogram")
+    return cnt
+
+
+def cutoff_eq1(t_percent: float, T: float, x_percent: float) -> float:
+    return float(lib().orc_cutoff_eq1(t_percent, T, x_percent))
+
+
+def cutoff_int(H: float) -> int:
+    return int(lib().orc_cutoff_int(H))
+
+
+def count_hot(cnt: np.ndarray, H: int) -> int:
+    cnt = _arr(cnt, np.uint32)
+    return int(lib().orc_count_hot(_p(cnt), C.c_int64(cnt.size), C.c_uint32(H)))
+
+
+def budget_cutoff(dim: int, cnts: List[np.ndarray], T: Sequence[int], n_profile_samples: int,
+                  budget_bytes: int, small_table_bytes: int = 1 << 20):
+    """Returns (c, H[z], n_hot[z])."""
+    nt = len(cnts)
+    cnts = [_arr(c, np.uint32) for c in cnts]
+    rows = np.array([c.size for c in cnts], dtype=np.int64)
+    Tn = np.array(T, dtype=np.int64)
+    c_out = C.c_int64(0)
+    H = np.zeros(nt, dtype=np.uint32)
+    nh = np.zeros(nt, dtype=np.int64)
+    rc = lib().orc_budget_cutoff(C.c_int32(nt), C.c_int32(dim), _p(rows), _ptr_array(cnts), _p(Tn),
+                                 C.c_int64(n_profile_samples), C.c_int64(budget_bytes),
+                                 C.c_int64(small_table_bytes), C.byref(c_out), _p(H), _p(nh))
+    _check(rc, "budget_cutoff")
+    return int(c_out.value), H, nh
+
+
+def classify(cnt: np.ndarray, H: int):
+    """Returns (remap int32[R], hot_ids int32[n_hot])."""
+    cnt = _arr(cnt, np.uint32)
+    remap = np.empty(cnt.size, dtype=np.int32)
+    hot_ids = np.empty(cnt.size, dtype=np.int32)
+    n = int(lib().orc_classify(_p(cnt), C.c_int64(cnt.size), C.c_uint32(H), _p(remap), _p(hot_ids)))
+    return remap, hot_ids[:n].copy()
+
+
+def gather_rows(W: np.ndarray, hot_ids: np.ndarray) -> np.ndarray:
+    W = _arr(W, np.float32)
+    hot_ids = _arr(hot_ids, np.int32)
+    out = np.empty((hot_ids.size, W.shape[1]), dtype=np.float32)
+    lib().orc_gather_rows(_p(W), C.c_int32(W.shape[1]), _p(hot_ids), C.c_int64(hot_ids.size), _p(out))
+    return out
+
+
+def w0(seed: int, table: int, row: int, dim: int, col: int) -> float:
+    return float(lib().orc_w0(seed, table, row, dim, col))
+
+
+def w0_rows(seed: int, table: int, rows: np.ndarray, dim: int) -> np.ndarray:
+    rows = _arr(rows, np.int64)
+    out = np.empty((rows.size, dim), dtype=np.float32)
+    lib().orc_w0_rows(C.c_uint64(seed), C.c_int32(table), _p(rows), C.c_int64(rows.size), C.c_int32(dim), _p(out))
+    return out
+
+
+# -- partition ----------------------------------------------------------------------
+def partition(rows: Sequence[int], n_samples: int, idx: List[np.ndarray],
+              offsets: List[Optional[np.ndarray]], remap: List[np.ndarray]):
+    """Returns (hot_samples, cold_samples, slots[z], hoffsets[z])."""
+    nt = len(rows)
+    idx = [_arr(a, np.int32) for a in idx]
+    offsets = [None if o is None else _arr(o, np.int32) for o in offsets]
+    remap = [_arr(r, np.int32) for r in remap]
+    rows_a = np.array(rows, dtype=np.int64)
+    hot = np.empty(n_samples, dtype=np.int32)
+    cold = np.empty(n_samples, dtype=np.int32)
+    slots = [np.empty(max(a.size, 1), dtype=np.int32) for a in idx]
+    hoff = [np.empty(n_samples + 1, dtype=np.int32) for _ in range(nt)]
+    nh = C.c_int64(0)
+    rc = lib().orc_partition(C.c_int32(nt), _p(rows_a), C.c_int64(n_samples), _ptr_array(idx),
+                             _ptr_array(offsets), _ptr_array(remap), _p(hot), _p(cold), C.byref(nh),
+                             _ptr_array(slots), _ptr_array(hoff))
+    _check(rc, "partition")
+    n = int(nh.value)
+    hoff = [h[:n + 1].copy() for h in hoff]
+    slots = [s[:int(h[-1])].copy() for s, h in zip(slots, hoff)]
+    return hot[:n].copy(), cold[:n_samples - n].copy(), slots, hoff
+
+
+# -- forward ------------------------------------------------------------------------
+def embbag_fwd(hotW: List[np.ndarray], n_samples: int, slots: List[np.ndarray],
+               offsets: List[Optional[np.ndarray]], want_mag: bool = False):
+    """out fp32[S][Tn][dim] (and sum|term| as fp64 of the same shape)."""
+    nt = len(hotW)
+    dim = hotW[0].shape[1]
+    out = np.zeros((n_samples, nt, dim), dtype=np.float32)
+    mag = np.zeros((n_samples, nt, dim), dtype=np.float64) if want_mag else None
+    for z in range(nt):
+        W = _arr(hotW[z], np.float32)
+        s = _arr(slots[z], np.int32)
+        o = None if offsets[z] is None else _arr(offsets[z], np.int32)
+        oz = out[:, z, :]
+        mz = mag[:, z, :] if want_mag else None
+        # pass a pointer to the first element of the strided view
+        rc = lib().orc_embbag_fwd(C.c_int64(W.shape[0]), C.c_int32(dim), _p(W), C.c_int64(n_samples),
+                                  _p(s), _p(o), C.c_void_p(oz.ctypes.data), C.c_int64(nt * dim),
+                                  None if mz is None else C.c_void_p(mz.ctypes.data), C.c_int64(nt * dim))
+        _check(rc, "embbag_fwd")
+    return (out, mag) if want_mag else out
+
+
+# -- backward -----------------------------------------------------------------------
+def sort_runs(slots: np.ndarray):
+    """Stable order by slot, distinct slots ascending, their multiplicities."""
+    slots = _arr(slots, np.int32)
+    n = slots.size
+    order = np.empty(max(n, 1), dtype=np.int32)
+    _check(lib().orc_sort_by_slot(_p(slots), C.c_int64(n), _p(order)), "sort_by_slot")
+    uniq = np.empty(max(n, 1), dtype=np.int32)
+    runlen = np.empty(max(n, 1), dtype=np.int32)
+    U = int(lib().orc_runs(_p(slots), _p(order), C.c_int64(n), _p(uniq), _p(runlen)))
+    return order[:n], uniq[:U].copy(), runlen[:U].copy()
+
+
+def bag_of(offsets: Optional[np.ndarray], n_samples: int, n_lookups: int) -> np.ndarray:
+    out = np.empty(max(n_lookups, 1), dtype=np.int32)
+    o = None if offsets is None else _arr(offsets, np.int32)
+    lib().orc_bag_of(_p(o), C.c_int64(n_samples), _p(out))
+    return out[:n_lookups]
+
+
+def run_grads(order: np.ndarray, bag: np.ndarray, runlen: np.ndarray, sel: np.ndarray,
+              gout: np.ndarray, table: int):
+    """Summed gradient (fp64) and sum of |g| of the selected runs of one table.
+    gout is fp32[S][Tn][dim]."""
+    gout = _arr(gout, np.float32)
+    _, nt, dim = gout.shape
+    order = _arr(order, np.int32)
+    bag = _arr(bag, np.int32)
+    runlen = _arr(runlen, np.int32)
+    sel = _arr(sel, np.int64)
+    run_start = np.zeros(runlen.size + 1, dtype=np.int64)
+    np.cumsum(runlen, out=run_start[1:])
+    G = np.zeros((sel.size, dim), dtype=np.float64)
+    Ga = np.zeros((sel.size, dim), dtype=np.float64)
+    base = gout.ctypes.data + table * dim * 4
+    lib().orc_run_grads(_p(order), _p(bag), _p(run_start), _p(runlen), _p(sel), C.c_int64(sel.size),
+                        C.c_void_p(base), C.c_int64(nt * dim), C.c_int32(dim), _p(G), _p(Ga))
+    return G, Ga
+
+
+def sgd_rows(W_rows: np.ndarray, G: np.ndarray, lr: float) -> np.ndarray:
+    W = _arr(W_rows, np.float32).copy()
+    G = _arr(G, np.float64)
+    lib().orc_sgd_rows(_p(W), _p(G), C.c_float(lr), C.c_int64(W.shape[0]), C.c_int32(W.shape[1]))
+    return W
+
+
+def embbag_bwd_sgd(hotW: List[np.ndarray], n_samples: int, slots: List[np.ndarray],
+                   offsets: List[Optional[np.ndarray]], gout: np.ndarray, lr: float,
+                   want_mag: bool = False):
+    """In place on hotW[z] (fp32, C-contiguous).  Returns (uniq[z], runlen[z], mag[z])."""
+    gout = _arr(gout, np.float32)
+    nt = len(hotW)
+    dim = hotW[0].shape[1]
+    assert gout.shape == (n_samples, nt, dim)
+    uniq_l, runlen_l, mag_l = [], [], []
+    for z in range(nt):
+        W = hotW[z]
+        assert W.dtype == np.float32 and W.flags.c_contiguous
+        s = _arr(slots[z], np.int32)
+        o = None if offsets[z] is None else _arr(offsets[z], np.int32)
+        n = s.size
+        uniq = np.empty(max(n, 1), dtype=np.int32)
+        runlen = np.empty(max(n, 1), dtype=np.int32)
+        mag = np.zeros((max(n, 1), dim), dtype=np.float64) if want_mag else None
+        nu = C.c_int64(0)
+        base = gout.ctypes.data + z * dim * 4
+        rc = lib().orc_embbag_bwd_sgd(C.c_int64(W.shape[0]), C.c_int32(dim), _p(W), C.c_int64(n_samples),
+                                      _p(s), _p(o), C.c_int64(n), C.c_void_p(base), C.c_int64(nt * dim),
+                                      C.c_float(lr), _p(uniq), _p(runlen), C.byref(nu), _p(mag))
+        _check(rc, "embbag_bwd_sgd")
+        U = int(nu.value)
+        uniq_l.append(uniq[:U].copy())
+        runlen_l.append(runlen[:U].copy())
+        mag_l.append(None if mag is None else mag[:U].copy())
+    return uniq_l, runlen_l, mag_l

@@ -1,0 +1,456 @@
+"""Pins of the CPU oracle against things other than itself (no GPU needed).
+
+Each test checks the oracle against what the paper or the mathematics fixes: the
+worked example of Eq. 1, brute force on tiny inputs, closed forms, invariants,
+dense-matrix forms computed by a library matmul, and PyTorch's stock CPU
+embedding-bag as a black box.  A plausible mistake anywhere in the oracle (a
+dropped term, > instead of >=, a transposed operand, an unstable sort) fails at
+least one of them.
+"""
+import math
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import fae_oracle as O
+from paper_2103_00686_amd import synth as S
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _golden(name):
+    out = {}
+    with open(os.path.join(GOLDEN, name)) as f:
+        for line in f:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            k, v = line.split()
+            out[k] = float(v)
+    return out
+
+
+# ----------------------------------------------------------------------------------
+# histogram (Embedding Logger, Sec. 4.1.2)
+# ----------------------------------------------------------------------------------
+def test_histogram_brute_force():
+    rng = np.random.default_rng(1)
+    R, n = 37, 500
+    idx = rng.integers(0, R, n).astype(np.int32)
+    cnt = O.histogram(R, idx)
+    brute = [sum(1 for j in range(n) if idx[j] == r) for r in range(R)]
+    assert cnt.tolist() == brute
+    assert int(cnt.sum()) == n
+
+
+def test_histogram_accumulates_and_is_order_free():
+    rng = np.random.default_rng(2)
+    R = 1000
+    idx = rng.zipf(1.3, 20000).astype(np.int64) % R
+    a = O.histogram(R, idx)
+    b = O.histogram(R, idx, a.copy())
+    assert (b == 2 * a).all()
+    c = O.histogram(R, rng.permutation(idx))
+    assert (c == a).all()
+
+
+def test_histogram_rejects_out_of_range():
+    with pytest.raises(O.OracleError) as e:
+        O.histogram(10, np.array([1, 10], dtype=np.int32))
+    assert e.value.code == O.ERANGE
+    with pytest.raises(O.OracleError):
+        O.histogram(10, np.array([-1], dtype=np.int32))
+    # nothing was counted when an index is bad
+    cnt = np.zeros(10, dtype=np.uint32)
+    with pytest.raises(O.OracleError):
+        O.histogram(10, np.array([3, 3, 11], dtype=np.int32), cnt)
+    assert cnt.sum() == 0
+
+
+# ----------------------------------------------------------------------------------
+# cutoff (Eq. 1, Eq. 2)
+# ----------------------------------------------------------------------------------
+def test_eq1_worked_example_from_paper():
+    g = _golden("eq1_worked_example.txt")
+    full = O.cutoff_eq1(g["t_percent"], g["T_samples"], 100.0)
+    assert full == pytest.approx(g["accesses_full_dataset"], rel=1e-12)
+    H = O.cutoff_eq1(g["t_percent"], g["T_samples"], g["x_percent"])
+    assert H == pytest.approx(g["H_zt"], rel=1e-12)
+    assert O.cutoff_int(H) == int(g["integer_cutoff"])
+
+
+def test_cutoff_int_is_ceiling_with_integer_guard():
+    assert O.cutoff_int(0.0) == 0
+    assert O.cutoff_int(4.0) == 4
+    assert O.cutoff_int(4.0000001) == 5
+    assert O.cutoff_int(3.9999999) == 4
+    assert O.cutoff_int(303.00000000000006) == 303   # an integer up to rounding stays put
+
+
+def test_hot_test_is_greater_or_equal():
+    cnt = np.array([0, 3, 4, 5, 4], dtype=np.uint32)
+    assert O.count_hot(cnt, 4) == 3            # a count equal to the cutoff is hot
+    remap, hot_ids = O.classify(cnt, 4)
+    assert remap.tolist() == [-1, -1, 0, 1, 2]
+    assert hot_ids.tolist() == [2, 3, 4]
+
+
+def _bytes_at(cnts, T, n_prof, dim, small, c):
+    """Independent numpy restatement of the budget objective."""
+    tot = 0
+    for cnt, t in zip(cnts, T):
+        if cnt.size * dim * 4 < small:
+            tot += cnt.size * dim * 4
+        else:
+            H = -((-c * t) // n_prof)
+            tot += int((cnt.astype(np.int64) >= H).sum()) * dim * 4
+    return tot
+
+
+def test_budget_cutoff_is_smallest_that_fits():
+    rng = np.random.default_rng(3)
+    dim, small = 4, 4096
+    cnts = [rng.poisson(lam, R).astype(np.uint32)
+            for lam, R in ((0.7, 5000), (3.0, 800), (1.5, 100), (6.0, 3000))]
+    n_prof = 1000
+    T = [int(c.sum()) for c in cnts]
+    sizes = [_bytes_at(cnts, T, n_prof, dim, small, c) for c in range(0, 40)]
+    assert all(a >= b for a, b in zip(sizes, sizes[1:]))          # monotone in c
+    for budget in (sizes[0], sizes[0] - 1, sizes[3], sizes[7] + 5, sizes[20]):
+        c, H, nh = O.budget_cutoff(dim, cnts, T, n_prof, budget, small)
+        assert _bytes_at(cnts, T, n_prof, dim, small, c) <= budget
+        assert c == 0 or _bytes_at(cnts, T, n_prof, dim, small, c - 1) > budget
+        for z, cnt in enumerate(cnts):
+            assert nh[z] == int((cnt >= H[z]).sum())
+        assert H[2] == 0 and nh[2] == 100      # the 1.6 KB table is small: wholly hot
+
+
+def test_budget_cutoff_zero_means_every_row_hot():
+    cnts = [np.zeros(50, dtype=np.uint32), np.arange(70, dtype=np.uint32)]
+    c, H, nh = O.budget_cutoff(8, cnts, [0, 2415], 10, 10**9, 0)
+    assert c == 0 and H.tolist() == [0, 0] and nh.tolist() == [50, 70]
+
+
+def test_budget_cutoff_one_hot_threshold_equals_c():
+    # one-hot table: T_z == n_profile_samples, so H_z == c
+    rng = np.random.default_rng(4)
+    cnt = rng.poisson(2.0, 4000).astype(np.uint32)
+    T = int(cnt.sum())
+    c, H, nh = O.budget_cutoff(16, [cnt], [T], T, 64 * 500, 0)
+    assert H[0] == c and nh[0] <= 500
+    assert int((cnt >= c - 1).sum()) > 500
+
+
+def test_budget_cutoff_reports_when_small_tables_alone_do_not_fit():
+    cnts = [np.ones(10, dtype=np.uint32)]
+    with pytest.raises(O.OracleError) as e:
+        O.budget_cutoff(4, cnts, [10], 10, 8, 1 << 20)
+    assert e.value.code == O.ENOSPC
+
+
+# ----------------------------------------------------------------------------------
+# classify / remap (Embedding Classifier, Sec. 4.2)
+# ----------------------------------------------------------------------------------
+def test_classify_invariants():
+    rng = np.random.default_rng(5)
+    cnt = rng.poisson(1.2, 3000).astype(np.uint32)
+    for H in (0, 1, 2, 5, 10**6):
+        remap, hot_ids = O.classify(cnt, H)
+        hot = remap >= 0
+        assert hot.sum() + (~hot).sum() == cnt.size              # hot + cold = all rows
+        assert hot.sum() == hot_ids.size == sum(1 for v in cnt if v >= H)
+        assert (np.diff(hot_ids) > 0).all()                       # ascending row order
+        assert (remap[hot_ids] == np.arange(hot_ids.size)).all()  # hot_ids[remap[r]] == r
+        assert (cnt[~hot] < H).all() and (cnt[hot] >= H).all()
+    remap, hot_ids = O.classify(cnt, 0)
+    assert (remap == np.arange(cnt.size)).all()                   # H = 0: identity
+
+
+def test_gather_rows():
+    W = np.arange(40, dtype=np.float32).reshape(10, 4)
+    out = O.gather_rows(W, np.array([7, 0, 3], dtype=np.int32))
+    assert out.tolist() == W[[7, 0, 3]].tolist()
+
+
+def test_w0_matches_generator_and_range():
+    rows = np.array([0, 1, 2, 99, 12345678, 99_999_999], dtype=np.int64)
+    for table in (0, 3, 25):
+        a = O.w0_rows(S.SEED, table, rows, 16)
+        b = S.w0_rows(S.SEED, table, torch.from_numpy(rows), 16).numpy()
+        assert a.tobytes() == b.tobytes()                          # two independent implementations
+    big = O.w0_rows(S.SEED, 1, np.arange(4000), 32)
+    assert big.min() >= -0.05 and big.max() < 0.05
+    assert abs(big.mean()) < 5e-4 and abs(big.std() - 0.1 / math.sqrt(12)) < 5e-4
+    assert O.w0(S.SEED, 1, 5, 32, 7) == big[5, 7]
+
+
+# ----------------------------------------------------------------------------------
+# partition (Input Classifier, Sec. 4.2)
+# ----------------------------------------------------------------------------------
+def _random_csr(rng, S_, R, maxlen, fixed=False):
+    if fixed:
+        return rng.integers(0, R, S_).astype(np.int32), None
+    lens = rng.integers(0, maxlen + 1, S_)
+    off = np.zeros(S_ + 1, dtype=np.int32)
+    off[1:] = np.cumsum(lens)
+    return rng.integers(0, R, int(off[-1])).astype(np.int32), off
+
+
+def test_partition_against_set_membership():
+    rng = np.random.default_rng(6)
+    rows = [50, 200, 30]
+    S_ = 300
+    cnts = [rng.poisson(1.0, R).astype(np.uint32) for R in rows]
+    rem, hot_sets = [], []
+    for c in cnts:
+        r, h = O.classify(c, 1)
+        rem.append(r)
+        hot_sets.append(set(h.tolist()))
+    idx, off = zip(*[_random_csr(rng, S_, R, 3, fixed=(z == 0)) for z, R in enumerate(rows)])
+    hs, cs, slots, hoff = O.partition(rows, S_, list(idx), list(off), rem)
+    # brute force, independent of remap: every index is a member of the hot-id set
+    want_hot = []
+    for s in range(S_):
+        ok = True
+        for z in range(3):
+            b, e = (s, s + 1) if off[z] is None else (off[z][s], off[z][s + 1])
+            ok &= all(int(i) in hot_sets[z] for i in idx[z][b:e])
+        if ok:
+            want_hot.append(s)
+    assert hs.tolist() == want_hot
+    assert sorted(hs.tolist() + cs.tolist()) == list(range(S_))     # disjoint cover
+    assert (np.diff(hs) > 0).all() and (np.diff(cs) > 0).all()      # stable
+    for z in range(3):
+        hot_ids = sorted(hot_sets[z])
+        w = 0
+        for h, s in enumerate(hs):
+            b, e = (s, s + 1) if off[z] is None else (off[z][s], off[z][s + 1])
+            assert hoff[z][h] == w
+            for i in idx[z][b:e]:
+                assert hot_ids[slots[z][w]] == i                    # slot names the same row
+                w += 1
+        assert hoff[z][len(hs)] == w == slots[z].size
+
+
+def test_partition_extremes_and_errors():
+    rng = np.random.default_rng(7)
+    rows = [40, 60]
+    cnts = [rng.poisson(1.0, R).astype(np.uint32) for R in rows]
+    idx, off = zip(*[_random_csr(rng, 100, R, 4) for R in rows])
+    all_hot = [O.classify(c, 0)[0] for c in cnts]
+    hs, cs, slots, _ = O.partition(rows, 100, list(idx), list(off), all_hot)
+    assert hs.tolist() == list(range(100)) and cs.size == 0
+    assert all((s == i).all() for s, i in zip(slots, idx))          # identity remap
+    none_hot = [O.classify(c, 2**32 - 1)[0] for c in cnts]
+    hs, cs, _, _ = O.partition(rows, 100, list(idx), list(off), none_hot)
+    # only samples whose bags are all empty stay hot
+    empty = [s for s in range(100) if all(o[s] == o[s + 1] for o in off)]
+    assert hs.tolist() == empty
+    bad = [idx[0].copy(), idx[1]]
+    bad[0][0] = 40
+    with pytest.raises(O.OracleError):
+        O.partition(rows, 100, bad, list(off), all_hot)
+
+
+def test_partition_all_hot_probability_closed_form():
+    """Sec. 3 (1): with independent accesses an input is hot with probability
+    prod_z p_z, and a batch of B inputs is all-hot with probability p^B."""
+    rng = np.random.default_rng(8)
+    R, Tn, S_, B = 1000, 4, 40000, 4
+    remap = [np.where(np.arange(R) < 900, np.arange(R), -1).astype(np.int32) for _ in range(Tn)]
+    idx = [rng.integers(0, R, S_).astype(np.int32) for _ in range(Tn)]
+    hs, cs, _, _ = O.partition([R] * Tn, S_, idx, [None] * Tn, remap)
+    p = 0.9 ** Tn
+    sd = math.sqrt(p * (1 - p) / S_)
+    assert abs(hs.size / S_ - p) < 5 * sd
+    hot_flag = np.zeros(S_, dtype=bool)
+    hot_flag[hs] = True
+    batches = hot_flag.reshape(-1, B).all(axis=1)
+    pb = p ** B
+    sdb = math.sqrt(pb * (1 - pb) / batches.size)
+    assert abs(batches.mean() - pb) < 5 * sdb
+
+
+# ----------------------------------------------------------------------------------
+# forward (hot mini-batch EmbeddingBag, sum pooling)
+# ----------------------------------------------------------------------------------
+def _multiplicity(slots, off, S_, n_hot):
+    A = np.zeros((S_, n_hot))
+    for s in range(S_):
+        b, e = (s, s + 1) if off is None else (off[s], off[s + 1])
+        for j in range(b, e):
+            A[s, slots[j]] += 1
+    return A
+
+
+def test_fwd_hand_computed():
+    W = np.array([[1, 2], [10, 20], [100, 200], [0.5, 0.25]], dtype=np.float32)
+    slots = np.array([0, 1, 1, 3, 2, 2, 2], dtype=np.int32)
+    off = np.array([0, 2, 2, 4, 7], dtype=np.int32)
+    out = O.embbag_fwd([W], 4, [slots], [off])
+    assert out[:, 0, :].tolist() == [[11, 22], [0, 0], [10.5, 20.25], [300, 600]]
+
+
+def test_fwd_length_one_is_a_bit_exact_gather():
+    rng = np.random.default_rng(9)
+    W = rng.standard_normal((64, 8)).astype(np.float32)
+    slots = rng.integers(0, 64, 200).astype(np.int32)
+    out = O.embbag_fwd([W], 200, [slots], [None])
+    assert out[:, 0, :].tobytes() == W[slots].tobytes()
+
+
+def test_fwd_equals_dense_matmul_on_integer_weights_bit_exact():
+    rng = np.random.default_rng(10)
+    n_hot, S_, dim = 50, 120, 6
+    W = rng.integers(-8, 9, (n_hot, dim)).astype(np.float32)
+    slots, off = _random_csr(rng, S_, n_hot, 9)
+    out, mag = O.embbag_fwd([W], S_, [slots], [off], want_mag=True)
+    A = _multiplicity(slots, off, S_, n_hot)
+    assert (out[:, 0, :].astype(np.float64) == A @ W.astype(np.float64)).all()
+    assert (mag[:, 0, :] == A @ np.abs(W).astype(np.float64)).all()
+
+
+def test_fwd_matches_torch_embedding_bag_black_box():
+    rng = np.random.default_rng(11)
+    n_hot, S_, dim = 300, 500, 16
+    W = (rng.random((n_hot, dim), dtype=np.float32) - 0.5) * 0.1
+    slots, off = _random_csr(rng, S_, n_hot, 12)
+    out = O.embbag_fwd([W], S_, [slots], [off])[:, 0, :]
+    ref = torch.nn.functional.embedding_bag(
+        torch.from_numpy(slots.astype(np.int64)), torch.from_numpy(W),
+        torch.from_numpy(off[:-1].astype(np.int64)), mode="sum").numpy()
+    assert np.allclose(out, ref, rtol=0, atol=2e-7)
+
+
+def test_fwd_two_tables_layout():
+    W0 = np.full((3, 2), 1.0, dtype=np.float32)
+    W1 = np.full((5, 2), 2.0, dtype=np.float32)
+    out = O.embbag_fwd([W0, W1], 2, [np.array([0, 1], np.int32), np.array([4, 4, 4], np.int32)],
+                       [None, np.array([0, 1, 3], np.int32)])
+    assert out.tolist() == [[[1, 1], [2, 2]], [[1, 1], [4, 4]]]
+
+
+# ----------------------------------------------------------------------------------
+# backward: sort, runs, summed gradient, SGD
+# ----------------------------------------------------------------------------------
+def test_sort_is_stable_and_runs_match_numpy_unique():
+    rng = np.random.default_rng(12)
+    slots = rng.integers(0, 40, 1000).astype(np.int32)
+    order, uniq, runlen = O.sort_runs(slots)
+    assert (np.diff(slots[order]) >= 0).all()
+    same = np.diff(slots[order]) == 0
+    assert (np.diff(order)[same] > 0).all()                       # equal slots keep position order
+    u, c = np.unique(slots, return_counts=True)
+    assert uniq.tolist() == u.tolist() and runlen.tolist() == c.tolist()
+    assert runlen.sum() == slots.size
+    assert order.tolist() == np.argsort(slots, kind="stable").tolist()
+
+
+def test_bag_of():
+    off = np.array([0, 2, 2, 5], dtype=np.int32)
+    assert O.bag_of(off, 3, 5).tolist() == [0, 0, 2, 2, 2]
+    assert O.bag_of(None, 4, 4).tolist() == [0, 1, 2, 3]
+
+
+def test_bwd_equals_dense_transpose_matmul_bit_exact_on_integers():
+    rng = np.random.default_rng(13)
+    n_hot, S_, dim, Tn = 30, 64, 4, 2
+    lr = 0.25                                   # power of two: every product is exact
+    Ws = [rng.integers(-8, 9, (n_hot, dim)).astype(np.float32) for _ in range(Tn)]
+    W0s = [w.copy() for w in Ws]
+    csr = [_random_csr(rng, S_, n_hot, 5) for _ in range(Tn)]
+    gout = rng.integers(-4, 5, (S_, Tn, dim)).astype(np.float32)
+    uniq, runlen, _ = O.embbag_bwd_sgd(Ws, S_, [c[0] for c in csr], [c[1] for c in csr], gout, lr)
+    for z in range(Tn):
+        A = _multiplicity(csr[z][0], csr[z][1], S_, n_hot)
+        G = A.T @ gout[:, z, :].astype(np.float64)               # textbook form of the gradient
+        want = (W0s[z].astype(np.float64) - lr * G).astype(np.float32)
+        assert Ws[z].tobytes() == want.tobytes()
+        touched = A.sum(axis=0) > 0
+        assert uniq[z].tolist() == np.nonzero(touched)[0].tolist()
+        assert runlen[z].tolist() == A.sum(axis=0)[touched].astype(int).tolist()
+        assert Ws[z][~touched].tobytes() == W0s[z][~touched].tobytes()   # untouched rows bit-identical
+
+
+def test_bwd_column_sum_invariant_and_run_grads():
+    rng = np.random.default_rng(14)
+    n_hot, S_, dim = 25, 80, 3
+    slots, off = _random_csr(rng, S_, n_hot, 6)
+    gout = rng.standard_normal((S_, 1, dim)).astype(np.float32)
+    order, uniq, runlen = O.sort_runs(slots)
+    bag = O.bag_of(off, S_, slots.size)
+    G, Ga = O.run_grads(order, bag, runlen, np.arange(uniq.size), gout, 0)
+    lens = np.diff(off)
+    want = (lens[:, None] * gout[:, 0, :].astype(np.float64)).sum(axis=0)
+    assert np.allclose(G.sum(axis=0), want, rtol=1e-12, atol=1e-12)
+    assert (Ga >= np.abs(G) - 1e-15).all()
+    # a subset selection returns the same rows
+    sel = np.array([uniq.size - 1, 0, 3])
+    G2, _ = O.run_grads(order, bag, runlen, sel, gout, 0)
+    assert (G2 == G[sel]).all()
+
+
+def test_bwd_lr_zero_leaves_table_bit_identical():
+    rng = np.random.default_rng(15)
+    W = rng.standard_normal((40, 8)).astype(np.float32)
+    W0 = W.copy()
+    slots, off = _random_csr(rng, 50, 40, 4)
+    gout = rng.standard_normal((50, 1, 8)).astype(np.float32)
+    O.embbag_bwd_sgd([W], 50, [slots], [off], gout, 0.0)
+    assert W.tobytes() == W0.tobytes()
+
+
+def test_bwd_no_duplicates_is_plain_sgd_within_one_ulp():
+    rng = np.random.default_rng(16)
+    n_hot, dim = 200, 8
+    W = rng.standard_normal((n_hot, dim)).astype(np.float32)
+    W0 = W.copy()
+    slots = rng.permutation(n_hot)[:100].astype(np.int32)
+    gout = rng.standard_normal((100, 1, dim)).astype(np.float32)
+    lr = np.float32(0.01)
+    O.embbag_bwd_sgd([W], 100, [slots], [None], gout, float(lr))
+    want = W0.copy()
+    want[slots] = W0[slots] - lr * gout[:, 0, :]                 # fp32 mul + sub
+    # two fp32 roundings (product, difference) against one: at most one ulp of the
+    # largest operand apart
+    big = np.maximum(np.abs(W0[slots]), np.maximum(np.abs(lr * gout[:, 0, :]), np.abs(want[slots])))
+    assert (np.abs(W[slots] - want[slots]) <= np.spacing(big.astype(np.float32))).all()
+    mask = np.ones(n_hot, bool)
+    mask[slots] = False
+    assert W[mask].tobytes() == W0[mask].tobytes()
+
+
+def test_bwd_duplicates_get_one_update_with_the_summed_gradient():
+    W = np.array([[1.0], [2.0]], dtype=np.float32)
+    slots = np.array([1, 0, 1, 1], dtype=np.int32)
+    off = np.array([0, 2, 4], dtype=np.int32)       # bag0 = {1,0}, bag1 = {1,1}
+    gout = np.array([[[1.0]], [[10.0]]], dtype=np.float32)
+    uniq, runlen, mag = O.embbag_bwd_sgd([W], 2, [slots], [off], gout, 0.5, want_mag=True)
+    assert uniq[0].tolist() == [0, 1] and runlen[0].tolist() == [1, 3]
+    assert W.tolist() == [[1.0 - 0.5 * 1.0], [2.0 - 0.5 * 21.0]]
+    assert mag[0].tolist() == [[1.0 + 0.5], [2.0 + 0.5 * 21.0]]
+
+
+def test_sgd_rows():
+    W = np.array([[1.0, 2.0]], dtype=np.float32)
+    out = O.sgd_rows(W, np.array([[4.0, -8.0]]), 0.125)
+    assert out.tolist() == [[0.5, 3.0]] and W.tolist() == [[1.0, 2.0]]
+
+
+# ----------------------------------------------------------------------------------
+# the synthetic workloads through the whole oracle (structure and paper-shaped skew)
+# ----------------------------------------------------------------------------------
+def test_cfg1_pipeline_shape():
+    w = S.workload(1)
+    prof = S.make_chunk(w, 0, 0, w.profile_samples)
+    cnt = O.histogram(w.rows[0], prof.indices[0].numpy())
+    remap, hot_ids = O.classify(cnt, w.cutoff)
+    share = cnt[hot_ids].sum() / cnt.sum()
+    # order of magnitude only: a per-cent-sized hot set serving most accesses (Sec. 1)
+    assert 500 < hot_ids.size < 5000 and 0.5 < share < 0.9
+    batch = S.make_chunk(w, 1, 0, w.batch)
+    hs, cs, slots, hoff = O.partition(w.rows, w.batch, [batch.indices[0].numpy()], [None], [remap])
+    assert 0.4 * w.batch < hs.size < 0.95 * w.batch
+    assert hs.size + cs.size == w.batch
