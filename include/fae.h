@@ -1,0 +1,180 @@
+/*
+ * libfae -- the GPU-resident hot path of the FAE (Frequently Accessed Embeddings)
+ * training method, arxiv 2103.00686, for AMD MI355X (gfx950).
+ *
+ * The path, in the paper's order (Sec. 4, Fig. 4 and Fig. 6):
+ *   profile (Embedding Logger)  ->  cutoff (Eq. 1 / budget L)  ->  classify + remap +
+ *   hot tables (Embedding Classifier, Embedding Replicator)  ->  partition (Input
+ *   Classifier)  ->  hot mini-batch forward (sum-pooled embedding bags)  ->  backward
+ *   (sort by row, sum duplicates)  ->  sparse SGD on the hot tables.
+ *
+ * Conventions
+ *   - C ABI, no exceptions, no global state.  Every call returns FAE_OK (0) or a
+ *     negative error code; fae_last_error() gives text for the last failure.
+ *   - Pointers named h_* are HOST pointers (small arrays of per-table values or of
+ *     per-table device pointers).  Every other pointer is a DEVICE pointer owned
+ *     by the caller.  The library allocates no user-visible device memory: bulk
+ *     scratch comes in through (ws, ws_bytes), sized by the *_workspace_bytes()
+ *     queries.  A context owns only one 4 KiB device block and one 4 KiB pinned
+ *     host block for status words and scalar read-backs.
+ *   - All kernels are enqueued on the stream given to fae_create().  Calls are
+ *     asynchronous unless documented as synchronising.
+ *   - Index validation happens on the device: an index outside [0, rows), a slot
+ *     outside [0, n_hot) or a malformed CSR is never dereferenced; it is skipped
+ *     and a sticky status bit is set, which the next synchronising call (or
+ *     fae_sync) returns as FAE_ERANGE / FAE_ENOSPC and then clears.
+ *   - Types: row ids, hot slots, sample ids and CSR offsets are int32; access
+ *     counts are uint32 (precondition: fewer than 2^32 accesses per row);
+ *     weights, pooled outputs and gradients are fp32, row-major.
+ *   - Limits: n_tables <= FAE_MAX_TABLES; dim >= 1 (dim % 4 == 0 takes the
+ *     16-byte vector path); lookups per table per call < 2^31; rows per table < 2^31.
+ */
+#ifndef FAE_H
+#define FAE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define FAE_MAX_TABLES 64
+
+#define FAE_OK 0
+#define FAE_EINVAL (-1) /* bad argument (null pointer, size, limit)                 */
+#define FAE_ERANGE (-2) /* index/slot out of range or malformed CSR (device-detected) */
+#define FAE_ENOSPC (-3) /* workspace or output capacity too small                   */
+#define FAE_EHIP   (-4) /* HIP runtime error; see fae_last_error()                  */
+
+typedef struct fae_ctx fae_ctx;
+
+/* Shape of a set of embedding tables: n_tables tables of h_rows[z] rows, all of
+ * row dimension dim.  For hot tables, h_rows[z] is n_hot_z. */
+typedef struct {
+    int32_t n_tables;
+    int32_t dim;
+    const int64_t *h_rows; /* host, [n_tables] */
+} fae_tables;
+
+/* A chunk of sparse inputs: per table a CSR over samples, table-major.
+ * h_offsets == NULL, or h_offsets[z] == NULL, means one lookup per sample in
+ * table z (then h_n_lookups[z] must equal n_samples). */
+typedef struct {
+    int64_t n_samples;
+    const int32_t *const *h_indices; /* host [n_tables] -> device int32[n_lookups_z]  */
+    const int32_t *const *h_offsets; /* host [n_tables] -> device int32[n_samples+1]  */
+    const int64_t *h_n_lookups;      /* host [n_tables]                               */
+} fae_batch;
+
+/* Where fae_build_hot_tables takes the weights of hot rows from. */
+#define FAE_SRC_DEVICE 0     /* h_W[z] -> device fp32[rows_z * dim], materialised table     */
+#define FAE_SRC_PROCEDURAL 1 /* virtual table: w(z,r,c) is a counter-based hash of seed     */
+typedef struct {
+    int32_t kind;
+    const float *const *h_W; /* FAE_SRC_DEVICE only */
+    uint64_t seed;           /* FAE_SRC_PROCEDURAL only */
+} fae_weight_src;
+
+/* Optional extra outputs of the backward for bit-exact checking: the distinct
+ * hot slots touched per table in ascending order and their multiplicities,
+ * concatenated table after table.  uniq/runlen need room for the total number of
+ * lookups; table_start gets n_tables+1 entries (start of each table's part). */
+typedef struct {
+    int32_t *uniq;
+    int32_t *runlen;
+    int32_t *table_start;
+} fae_bwd_debug;
+
+/* ---- context -------------------------------------------------------------- */
+/* Bind a context to a device and a HIP stream (hipStream_t passed as void*;
+ * NULL = the default stream).  Allocates the two 4 KiB status blocks. */
+int32_t fae_create(fae_ctx **out, int32_t device, void *hip_stream);
+void fae_destroy(fae_ctx *ctx);
+const char *fae_last_error(const fae_ctx *ctx);
+const char *fae_version(void);
+/* Wait for the stream; return and clear the deferred device status. */
+int32_t fae_sync(fae_ctx *ctx);
+/* Tuning/ablation switches, e.g. ("profile_variant", 0=auto 1=global atomics
+ * 2=LDS-privatised), ("fwd_variant", 0=auto 1=group-per-bag 2=wave-per-bag),
+ * ("sort_variant", 0=auto 1=global radix 2=LDS per table). */
+int32_t fae_set_option(fae_ctx *ctx, const char *name, int64_t value);
+
+/* ---- a1: Embedding Logger (Sec. 4.1.2) ------------------------------------- */
+/* counts_z[r] += number of lookups of `chunk` into row r of table z.  The caller
+ * zeroes the counters before the first chunk; calls accumulate.  Asynchronous. */
+int32_t fae_profile(fae_ctx *ctx, const fae_tables *tables, const fae_batch *chunk,
+                    uint32_t *const *h_counts /* host [n_tables] -> device uint32[rows_z] */);
+
+/* ---- a2: hot cutoff (Eq. 1, Eq. 2; budget L of Sec. 4.1) ------------------- */
+/* Budget mode.  Tables with rows_z*dim*4 < small_table_bytes are wholly hot
+ * (cutoff 0).  Every other table uses H_z(c) = ceil(c * h_T[z] / n_profile_samples)
+ * and a row is hot iff count >= H_z.  Finds the smallest integer c >= 0 whose hot
+ * rows (small tables included) fit budget_bytes.  h_T[z] is the number of profiled
+ * lookups into table z.  Outputs (host): *h_c_out, h_cutoff_out[z], h_n_hot_out[z].
+ * Synchronises.  FAE_ENOSPC if the small tables alone exceed the budget. */
+size_t fae_choose_cutoff_workspace_bytes(const fae_tables *tables);
+int32_t fae_choose_cutoff(fae_ctx *ctx, const fae_tables *tables, const uint32_t *const *h_counts,
+                          const int64_t *h_T, int64_t n_profile_samples, int64_t budget_bytes,
+                          int64_t small_table_bytes, int64_t *h_c_out, uint32_t *h_cutoff_out,
+                          int64_t *h_n_hot_out, void *ws, size_t ws_bytes);
+/* Explicit mode helper: number of rows with count >= h_cutoff[z].  Synchronises. */
+int32_t fae_count_hot(fae_ctx *ctx, const fae_tables *tables, const uint32_t *const *h_counts,
+                      const uint32_t *h_cutoff, int64_t *h_n_hot_out, void *ws, size_t ws_bytes);
+
+/* ---- a3 + a4: Embedding Classifier and Replicator (Sec. 4.2, Sec. 4) ------- */
+/* Tags every row hot (count >= h_cutoff[z]) or cold in one pass, gives hot rows
+ * consecutive slots in ascending row order, and fills the hot tables:
+ *   remap_z[r]   = slot of r, or -1 if cold          (device int32[rows_z])
+ *   hot_ids_z[s] = row id held by slot s               (device int32[h_cap[z]])
+ *   hotW_z[s][:] = weights of row hot_ids_z[s]         (device fp32[h_cap[z]*dim])
+ * h_cap[z] is the capacity (in rows) of hot_ids_z/hotW_z; if a table has more hot
+ * rows than capacity nothing is written past it and FAE_ENOSPC is returned.
+ * h_n_hot_out[z] (host) receives the hot-row counts.  Synchronises. */
+size_t fae_build_workspace_bytes(const fae_tables *tables);
+int32_t fae_build_hot_tables(fae_ctx *ctx, const fae_tables *tables, const uint32_t *const *h_counts,
+                             const uint32_t *h_cutoff, const fae_weight_src *src,
+                             int32_t *const *h_remap, int32_t *const *h_hot_ids,
+                             float *const *h_hotW, const int64_t *h_cap, int64_t *h_n_hot_out,
+                             void *ws, size_t ws_bytes);
+
+/* ---- a5: Input Classifier (Sec. 4.2) --------------------------------------- */
+/* A sample is hot iff every lookup in every table hits a hot row.  Outputs:
+ *   hot_samples  int32[n_samples]  ids of hot samples, ascending (first *h_n_hot_samples valid)
+ *   cold_samples int32[n_samples]  ids of cold samples, ascending
+ *   h_slots[z]    -> device int32[n_lookups_z]  hot slots of the hot samples' lookups, in order
+ *   h_hoffsets[z] -> device int32[n_samples+1]  CSR offsets of the hot sub-batch
+ *   h_n_hot_lookups[z] (host) = lookups of the hot sub-batch in table z
+ * The hot sub-batch (h_slots, h_hoffsets, *h_n_hot_samples, h_n_hot_lookups) is a
+ * fae_batch over the hot tables; consecutive slices of it are the hot mini-batches.
+ * Synchronises. */
+size_t fae_partition_workspace_bytes(const fae_tables *tables, int64_t n_samples);
+int32_t fae_partition_batch(fae_ctx *ctx, const fae_tables *tables, const fae_batch *in,
+                            const int32_t *const *h_remap, int32_t *hot_samples,
+                            int32_t *cold_samples, int64_t *h_n_hot_samples,
+                            int32_t *const *h_slots, int32_t *const *h_hoffsets,
+                            int64_t *h_n_hot_lookups, void *ws, size_t ws_bytes);
+
+/* ---- a6: hot mini-batch forward (Fig. 2; sum pooling) ---------------------- */
+/* out[s*out_row_stride + z*dim + c] = sum over the lookups j of bag (s,z) of
+ * hotW_z[slot_j][c]; repeated slots count with multiplicity; an empty bag gives
+ * zeros.  hot_tables->h_rows[z] = n_hot_z; hot_batch->h_indices hold hot slots.
+ * out_row_stride (in floats) >= n_tables*dim.  Asynchronous. */
+int32_t fae_embbag_fwd(fae_ctx *ctx, const fae_tables *hot_tables, const float *const *h_hotW,
+                       const fae_batch *hot_batch, float *out, int64_t out_row_stride);
+
+/* ---- a7 + a8: backward and sparse SGD on the GPU (Sec. 2.2, Sec. 6.2) ------ */
+/* Per table: sorts the lookups by hot slot (stable), sums the upstream gradient
+ * rows gout[s*gout_row_stride + z*dim + :] of duplicate slots, and applies
+ * hotW_z[slot][:] -= lr * G[slot][:] once per distinct slot; untouched rows are
+ * not written.  dbg may be NULL.  Asynchronous. */
+size_t fae_bwd_workspace_bytes(const fae_tables *hot_tables, int64_t n_samples,
+                               const int64_t *h_n_lookups);
+int32_t fae_embbag_bwd_sgd(fae_ctx *ctx, const fae_tables *hot_tables, float *const *h_hotW,
+                           const fae_batch *hot_batch, const float *gout, int64_t gout_row_stride,
+                           float lr, const fae_bwd_debug *dbg, void *ws, size_t ws_bytes);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FAE_H */

@@ -1,0 +1,280 @@
+"""Thin ctypes binding of libfae.so: same names as the C ABI (include/fae.h), argument
+marshalling only.  Every step of the path runs in the library's HIP kernels; torch
+is used for device memory and the stream.  There is no CPU fallback: if the
+library is missing and cannot be built, importing a function raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import List, Optional, Sequence
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libfae.so")
+
+FAE_OK, FAE_EINVAL, FAE_ERANGE, FAE_ENOSPC, FAE_EHIP = 0, -1, -2, -3, -4
+FAE_MAX_TABLES = 64
+FAE_SRC_DEVICE, FAE_SRC_PROCEDURAL = 0, 1
+
+EXPORTS = [
+    "fae_create", "fae_destroy", "fae_last_error", "fae_version", "fae_sync", "fae_set_option",
+    "fae_profile", "fae_choose_cutoff_workspace_bytes", "fae_choose_cutoff", "fae_count_hot",
+    "fae_build_workspace_bytes", "fae_build_hot_tables", "fae_partition_workspace_bytes",
+    "fae_partition_batch", "fae_embbag_fwd", "fae_bwd_workspace_bytes", "fae_embbag_bwd_sgd",
+]
+
+
+class FaeError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"libfae error {code}: {msg}")
+        self.code = code
+
+
+class _Tables(C.Structure):
+    _fields_ = [("n_tables", C.c_int32), ("dim", C.c_int32), ("h_rows", C.POINTER(C.c_int64))]
+
+
+class _Batch(C.Structure):
+    _fields_ = [("n_samples", C.c_int64), ("h_indices", C.POINTER(C.c_void_p)),
+                ("h_offsets", C.POINTER(C.c_void_p)), ("h_n_lookups", C.POINTER(C.c_int64))]
+
+
+class _WeightSrc(C.Structure):
+    _fields_ = [("kind", C.c_int32), ("h_W", C.POINTER(C.c_void_p)), ("seed", C.c_uint64)]
+
+
+class _BwdDebug(C.Structure):
+    _fields_ = [("uniq", C.c_void_p), ("runlen", C.c_void_p), ("table_start", C.c_void_p)]
+
+
+_lib = None
+
+
+def load():
+    """Load libfae.so (building it first if it has never been built)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        from . import build as _build
+        _build.build()
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError("libfae.so is missing and could not be built; run __graft_entry__.build()")
+    lib = C.CDLL(LIB_PATH)
+    lib.fae_last_error.restype = C.c_char_p
+    lib.fae_last_error.argtypes = [C.c_void_p]
+    lib.fae_version.restype = C.c_char_p
+    for name in ("fae_choose_cutoff_workspace_bytes", "fae_build_workspace_bytes",
+                 "fae_partition_workspace_bytes", "fae_bwd_workspace_bytes"):
+        getattr(lib, name).restype = C.c_size_t
+    lib.fae_destroy.restype = None
+    _lib = lib
+    return lib
+
+
+# ------------------------------------------------------------------------------------
+# marshalling helpers
+# ------------------------------------------------------------------------------------
+@dataclass
+class Tables:
+    rows: Sequence[int]
+    dim: int
+
+    def c(self):
+        rows = (C.c_int64 * len(self.rows))(*[int(r) for r in self.rows])
+        t = _Tables(len(self.rows), int(self.dim), rows)
+        t._keep = rows
+        return t
+
+
+@dataclass
+class Batch:
+    n_samples: int
+    indices: List[torch.Tensor]                 # per table, device int32
+    offsets: List[Optional[torch.Tensor]]       # per table, device int32[S+1] or None
+    n_lookups: Sequence[int]
+
+    def c(self):
+        nt = len(self.indices)
+        idx = _ptrs(self.indices, torch.int32)
+        off = _ptrs(self.offsets, torch.int32) if any(o is not None for o in self.offsets) else None
+        nl = (C.c_int64 * nt)(*[int(n) for n in self.n_lookups])
+        b = _Batch(int(self.n_samples), idx, off, nl)
+        b._keep = (idx, off, nl)
+        return b
+
+
+def _ptrs(tensors: Sequence[Optional[torch.Tensor]], dtype):
+    arr = (C.c_void_p * len(tensors))()
+    for i, t in enumerate(tensors):
+        if t is None:
+            arr[i] = None
+            continue
+        if t.dtype != dtype or not t.is_contiguous() or not t.is_cuda:
+            raise TypeError(f"tensor {i}: need a contiguous device tensor of {dtype}, got {t.dtype} on {t.device}")
+        arr[i] = t.data_ptr() if t.numel() > 0 else None
+    return arr
+
+
+def _ptr(t: Optional[torch.Tensor], dtype):
+    if t is None:
+        return None
+    if t.dtype != dtype or not t.is_contiguous() or not t.is_cuda:
+        raise TypeError(f"need a contiguous device tensor of {dtype}, got {t.dtype} on {t.device}")
+    return C.c_void_p(t.data_ptr())
+
+
+# ------------------------------------------------------------------------------------
+# the ABI, name for name
+# ------------------------------------------------------------------------------------
+class Context:
+    """Owns a fae_ctx bound to a device and a stream (default: torch's current stream)."""
+
+    def __init__(self, device: int = 0, stream: Optional[int] = None):
+        lib = load()
+        if not torch.cuda.is_available():
+            raise RuntimeError("libfae needs a GPU: torch.cuda.is_available() is False")
+        if stream is None:
+            stream = torch.cuda.current_stream(device).cuda_stream
+        self.device = device
+        self._h = C.c_void_p()
+        rc = lib.fae_create(C.byref(self._h), C.c_int32(device), C.c_void_p(stream))
+        if rc != FAE_OK:
+            raise FaeError(rc, "fae_create failed")
+
+    def close(self):
+        if self._h:
+            load().fae_destroy(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def check(self, rc: int):
+        if rc != FAE_OK:
+            raise FaeError(rc, load().fae_last_error(self._h).decode())
+
+
+def fae_version() -> str:
+    return load().fae_version().decode()
+
+
+def fae_sync(ctx: Context):
+    ctx.check(load().fae_sync(ctx._h))
+
+
+def fae_set_option(ctx: Context, name: str, value: int):
+    ctx.check(load().fae_set_option(ctx._h, name.encode(), C.c_int64(value)))
+
+
+def fae_profile(ctx: Context, tables: Tables, chunk: Batch, counts: List[torch.Tensor]):
+    t, b = tables.c(), chunk.c()
+    ctx.check(load().fae_profile(ctx._h, C.byref(t), C.byref(b), _ptrs(counts, torch.int32)))
+
+
+def fae_choose_cutoff_workspace_bytes(tables: Tables) -> int:
+    t = tables.c()
+    return int(load().fae_choose_cutoff_workspace_bytes(C.byref(t)))
+
+
+def fae_choose_cutoff(ctx: Context, tables: Tables, counts: List[torch.Tensor], T: Sequence[int],
+                      n_profile_samples: int, budget_bytes: int, small_table_bytes: int, ws: torch.Tensor):
+    """Returns (c, cutoff[z], n_hot[z]) as Python ints."""
+    nt = len(tables.rows)
+    t = tables.c()
+    Ta = (C.c_int64 * nt)(*[int(v) for v in T])
+    c_out = C.c_int64(0)
+    cut = (C.c_uint32 * nt)()
+    nh = (C.c_int64 * nt)()
+    ctx.check(load().fae_choose_cutoff(ctx._h, C.byref(t), _ptrs(counts, torch.int32), Ta,
+                                       C.c_int64(n_profile_samples), C.c_int64(budget_bytes),
+                                       C.c_int64(small_table_bytes), C.byref(c_out), cut, nh,
+                                       _ptr(ws, torch.uint8), C.c_size_t(ws.numel())))
+    return int(c_out.value), list(cut), list(nh)
+
+
+def fae_count_hot(ctx: Context, tables: Tables, counts: List[torch.Tensor], cutoff: Sequence[int],
+                  ws: torch.Tensor) -> List[int]:
+    nt = len(tables.rows)
+    t = tables.c()
+    cut = (C.c_uint32 * nt)(*[int(v) for v in cutoff])
+    nh = (C.c_int64 * nt)()
+    ctx.check(load().fae_count_hot(ctx._h, C.byref(t), _ptrs(counts, torch.int32), cut, nh,
+                                   _ptr(ws, torch.uint8), C.c_size_t(ws.numel())))
+    return list(nh)
+
+
+def fae_build_workspace_bytes(tables: Tables) -> int:
+    t = tables.c()
+    return int(load().fae_build_workspace_bytes(C.byref(t)))
+
+
+def fae_build_hot_tables(ctx: Context, tables: Tables, counts: List[torch.Tensor], cutoff: Sequence[int],
+                         src_kind: int, src_W: Optional[List[torch.Tensor]], seed: int,
+                         remap: List[torch.Tensor], hot_ids: List[torch.Tensor], hotW: List[torch.Tensor],
+                         cap: Sequence[int], ws: torch.Tensor) -> List[int]:
+    nt = len(tables.rows)
+    t = tables.c()
+    cut = (C.c_uint32 * nt)(*[int(v) for v in cutoff])
+    capa = (C.c_int64 * nt)(*[int(v) for v in cap])
+    nh = (C.c_int64 * nt)()
+    wp = _ptrs(src_W, torch.float32) if src_W is not None else None
+    src = _WeightSrc(int(src_kind), wp, C.c_uint64(seed & ((1 << 64) - 1)))
+    ctx.check(load().fae_build_hot_tables(ctx._h, C.byref(t), _ptrs(counts, torch.int32), cut, C.byref(src),
+                                          _ptrs(remap, torch.int32), _ptrs(hot_ids, torch.int32),
+                                          _ptrs(hotW, torch.float32), capa, nh,
+                                          _ptr(ws, torch.uint8), C.c_size_t(ws.numel())))
+    return list(nh)
+
+
+def fae_partition_workspace_bytes(tables: Tables, n_samples: int) -> int:
+    t = tables.c()
+    return int(load().fae_partition_workspace_bytes(C.byref(t), C.c_int64(n_samples)))
+
+
+def fae_partition_batch(ctx: Context, tables: Tables, batch: Batch, remap: List[torch.Tensor],
+                        hot_samples: torch.Tensor, cold_samples: torch.Tensor,
+                        slots: List[torch.Tensor], hoffsets: List[torch.Tensor], ws: torch.Tensor):
+    """Returns (n_hot_samples, n_hot_lookups[z])."""
+    nt = len(tables.rows)
+    t, b = tables.c(), batch.c()
+    n_hot = C.c_int64(0)
+    nl = (C.c_int64 * nt)()
+    ctx.check(load().fae_partition_batch(ctx._h, C.byref(t), C.byref(b), _ptrs(remap, torch.int32),
+                                         _ptr(hot_samples, torch.int32), _ptr(cold_samples, torch.int32),
+                                         C.byref(n_hot), _ptrs(slots, torch.int32), _ptrs(hoffsets, torch.int32),
+                                         nl, _ptr(ws, torch.uint8), C.c_size_t(ws.numel())))
+    return int(n_hot.value), list(nl)
+
+
+def fae_embbag_fwd(ctx: Context, hot_tables: Tables, hotW: List[torch.Tensor], hot_batch: Batch,
+                   out: torch.Tensor, out_row_stride: int):
+    t, b = hot_tables.c(), hot_batch.c()
+    ctx.check(load().fae_embbag_fwd(ctx._h, C.byref(t), _ptrs(hotW, torch.float32), C.byref(b),
+                                    _ptr(out, torch.float32), C.c_int64(out_row_stride)))
+
+
+def fae_bwd_workspace_bytes(hot_tables: Tables, n_samples: int, n_lookups: Sequence[int]) -> int:
+    t = hot_tables.c()
+    nl = (C.c_int64 * len(n_lookups))(*[int(n) for n in n_lookups])
+    return int(load().fae_bwd_workspace_bytes(C.byref(t), C.c_int64(n_samples), nl))
+
+
+def fae_embbag_bwd_sgd(ctx: Context, hot_tables: Tables, hotW: List[torch.Tensor], hot_batch: Batch,
+                       gout: torch.Tensor, gout_row_stride: int, lr: float, ws: torch.Tensor,
+                       dbg_uniq: Optional[torch.Tensor] = None, dbg_runlen: Optional[torch.Tensor] = None,
+                       dbg_table_start: Optional[torch.Tensor] = None):
+    t, b = hot_tables.c(), hot_batch.c()
+    dbg = None
+    if dbg_uniq is not None:
+        d = _BwdDebug(_ptr(dbg_uniq, torch.int32), _ptr(dbg_runlen, torch.int32), _ptr(dbg_table_start, torch.int32))
+        dbg = C.byref(d)
+    ctx.check(load().fae_embbag_bwd_sgd(ctx._h, C.byref(t), _ptrs(hotW, torch.float32), C.byref(b),
+                                        _ptr(gout, torch.float32), C.c_int64(gout_row_stride), C.c_float(lr),
+                                        dbg, _ptr(ws, torch.uint8), C.c_size_t(ws.numel())))

@@ -1,0 +1,167 @@
+// Context, error reporting and argument validation of libfae.
+#include <stdarg.h>
+#include <stdlib.h>
+
+#include "fae_internal.h"
+
+int32_t fae_fail(fae_ctx *ctx, int32_t code, const char *fmt, ...)
+{
+    if (ctx) {
+        va_list ap;
+        va_start(ap, fmt);
+        vsnprintf(ctx->err, sizeof(ctx->err), fmt, ap);
+        va_end(ap);
+    }
+    return code;
+}
+
+__global__ void fae_clear_words_kernel(uint32_t *p, int n)
+{
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n)
+        p[i] = 0u;
+}
+
+extern "C" int32_t fae_create(fae_ctx **out, int32_t device, void *hip_stream)
+{
+    if (!out)
+        return FAE_EINVAL;
+    *out = nullptr;
+    int n_dev = 0;
+    if (hipGetDeviceCount(&n_dev) != hipSuccess || device < 0 || device >= n_dev)
+        return FAE_EHIP;
+    fae_ctx *ctx = (fae_ctx *)calloc(1, sizeof(fae_ctx));
+    if (!ctx)
+        return FAE_ENOSPC;
+    ctx->device = device;
+    ctx->stream = (hipStream_t)hip_stream;
+    if (hipSetDevice(device) != hipSuccess) {
+        free(ctx);
+        return FAE_EHIP;
+    }
+    hipDeviceProp_t prop;
+    if (hipGetDeviceProperties(&prop, device) != hipSuccess) {
+        free(ctx);
+        return FAE_EHIP;
+    }
+    ctx->n_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+    if (hipMalloc((void **)&ctx->d_block, FAE_BLK_WORDS * sizeof(uint32_t)) != hipSuccess) {
+        free(ctx);
+        return FAE_EHIP;
+    }
+    if (hipHostMalloc((void **)&ctx->h_block, FAE_BLK_WORDS * sizeof(uint32_t), hipHostMallocDefault) !=
+        hipSuccess) {
+        (void)hipFree(ctx->d_block);
+        free(ctx);
+        return FAE_EHIP;
+    }
+    memset(ctx->h_block, 0, FAE_BLK_WORDS * sizeof(uint32_t));
+    hipLaunchKernelGGL(fae_clear_words_kernel, dim3(FAE_BLK_WORDS / 256), dim3(256), 0, ctx->stream,
+                       ctx->d_block, FAE_BLK_WORDS);
+    if (hipGetLastError() != hipSuccess || hipStreamSynchronize(ctx->stream) != hipSuccess) {
+        (void)hipFree(ctx->d_block);
+        (void)hipHostFree(ctx->h_block);
+        free(ctx);
+        return FAE_EHIP;
+    }
+    *out = ctx;
+    return FAE_OK;
+}
+
+extern "C" void fae_destroy(fae_ctx *ctx)
+{
+    if (!ctx)
+        return;
+    (void)hipSetDevice(ctx->device);
+    (void)hipStreamSynchronize(ctx->stream);
+    (void)hipFree(ctx->d_block);
+    (void)hipHostFree(ctx->h_block);
+    free(ctx);
+}
+
+extern "C" const char *fae_last_error(const fae_ctx *ctx) { return ctx ? ctx->err : "null context"; }
+
+extern "C" const char *fae_version(void) { return "libfae 0.1 (gfx950)"; }
+
+extern "C" int32_t fae_set_option(fae_ctx *ctx, const char *name, int64_t value)
+{
+    if (!ctx || !name)
+        return FAE_EINVAL;
+    if (!strcmp(name, "profile_variant") && value >= 0 && value <= 2)
+        ctx->opt_profile = value;
+    else if (!strcmp(name, "fwd_variant") && value >= 0 && value <= 2)
+        ctx->opt_fwd = value;
+    else if (!strcmp(name, "sort_variant") && value >= 0 && value <= 2)
+        ctx->opt_sort = value;
+    else
+        return fae_fail(ctx, FAE_EINVAL, "fae_set_option: unknown option or value: %s=%lld", name,
+                        (long long)value);
+    return FAE_OK;
+}
+
+int32_t fae_readback(fae_ctx *ctx, int first, int n)
+{
+    FAE_HIP(ctx, hipMemcpyAsync(ctx->h_block + first, ctx->d_block + first, (size_t)n * sizeof(uint32_t),
+                                hipMemcpyDeviceToHost, ctx->stream));
+    FAE_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    return FAE_OK;
+}
+
+int32_t fae_sync_status(fae_ctx *ctx)
+{
+    int32_t rc = fae_readback(ctx, FAE_BLK_STATUS, 1);
+    if (rc != FAE_OK)
+        return rc;
+    uint32_t st = ctx->h_block[FAE_BLK_STATUS];
+    if (st == 0)
+        return FAE_OK;
+    hipLaunchKernelGGL(fae_clear_words_kernel, dim3(1), dim3(64), 0, ctx->stream, ctx->d_block, 1);
+    FAE_LAUNCH_CHECK(ctx);
+    FAE_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    if (st & FAE_STATUS_ERANGE)
+        return fae_fail(ctx, FAE_ERANGE, "device detected an index/slot out of range or a malformed CSR");
+    return fae_fail(ctx, FAE_ENOSPC, "device detected an output capacity overflow");
+}
+
+extern "C" int32_t fae_sync(fae_ctx *ctx)
+{
+    if (!ctx)
+        return FAE_EINVAL;
+    return fae_sync_status(ctx);
+}
+
+int32_t fae_check_tables(fae_ctx *ctx, const fae_tables *t, const char *who)
+{
+    if (!ctx)
+        return FAE_EINVAL;
+    if (!t || !t->h_rows)
+        return fae_fail(ctx, FAE_EINVAL, "%s: null tables", who);
+    if (t->n_tables < 1 || t->n_tables > FAE_MAX_TABLES)
+        return fae_fail(ctx, FAE_EINVAL, "%s: n_tables=%d outside [1,%d]", who, t->n_tables, FAE_MAX_TABLES);
+    if (t->dim < 1 || t->dim > 65536)
+        return fae_fail(ctx, FAE_EINVAL, "%s: dim=%d outside [1,65536]", who, t->dim);
+    for (int z = 0; z < t->n_tables; ++z)
+        if (t->h_rows[z] < 0 || t->h_rows[z] >= 2147483647LL)
+            return fae_fail(ctx, FAE_EINVAL, "%s: rows[%d]=%lld outside [0,2^31-1)", who, z,
+                            (long long)t->h_rows[z]);
+    return FAE_OK;
+}
+
+int32_t fae_check_batch(fae_ctx *ctx, const fae_tables *t, const fae_batch *b, const char *who)
+{
+    if (!b || !b->h_indices || !b->h_n_lookups)
+        return fae_fail(ctx, FAE_EINVAL, "%s: null batch", who);
+    if (b->n_samples < 0 || b->n_samples >= 2147483647LL)
+        return fae_fail(ctx, FAE_EINVAL, "%s: n_samples=%lld outside [0,2^31-1)", who, (long long)b->n_samples);
+    for (int z = 0; z < t->n_tables; ++z) {
+        int64_t nl = b->h_n_lookups[z];
+        if (nl < 0 || nl >= 2147483647LL)
+            return fae_fail(ctx, FAE_EINVAL, "%s: n_lookups[%d]=%lld outside [0,2^31-1)", who, z, (long long)nl);
+        bool one_hot = !b->h_offsets || !b->h_offsets[z];
+        if (one_hot && nl != b->n_samples)
+            return fae_fail(ctx, FAE_EINVAL, "%s: table %d has no offsets but n_lookups != n_samples", who, z);
+        if (nl > 0 && !b->h_indices[z])
+            return fae_fail(ctx, FAE_EINVAL, "%s: null indices for table %d", who, z);
+    }
+    return FAE_OK;
+}

@@ -1,0 +1,245 @@
+// Hot mini-batch forward: row gather + sum pooling over HBM-resident hot tables.
+//
+// One launch covers every table of the batch.  Two lane mappings:
+//   group-per-bag : LPR adjacent lanes own one bag, each lane one 16-byte column
+//                   slice; bags of a wave sit side by side (best for one-hot / short bags);
+//   wave-per-bag  : the 64/LPR lane groups of a wave take alternate entries of one
+//                   bag and are combined with cross-lane shuffles (best for long,
+//                   uneven bags: no lane group idles while its neighbour finishes).
+// Bandwidth bound: per lookup one slot (4 B) and one row (dim*4 B) are read, per bag
+// one row is written.  No arithmetic beyond one add per loaded float.
+#include "fae_internal.h"
+
+struct FwdArgs {
+    const float *W[FAE_MAX_TABLES];
+    const int32_t *slots[FAE_MAX_TABLES];
+    const int32_t *offsets[FAE_MAX_TABLES];
+    int32_t n_hot[FAE_MAX_TABLES];
+    int32_t n_lookups[FAE_MAX_TABLES];
+    int32_t blk_start[FAE_MAX_TABLES + 1];
+    int32_t n_tables;
+    int32_t dim;
+    int32_t n_samples;
+    int64_t out_stride;
+    float *out;
+    uint32_t *status;
+};
+
+template <typename V> struct vec_ops;
+template <> struct vec_ops<float4> {
+    static __device__ __forceinline__ float4 zero() { return make_float4(0.f, 0.f, 0.f, 0.f); }
+    static __device__ __forceinline__ void add(float4 &a, const float4 &b)
+    {
+        a.x += b.x;
+        a.y += b.y;
+        a.z += b.z;
+        a.w += b.w;
+    }
+    static __device__ __forceinline__ float4 shfl_xor(const float4 &a, int m)
+    {
+        return make_float4(__shfl_xor(a.x, m, FAE_WAVE), __shfl_xor(a.y, m, FAE_WAVE),
+                           __shfl_xor(a.z, m, FAE_WAVE), __shfl_xor(a.w, m, FAE_WAVE));
+    }
+};
+template <> struct vec_ops<float> {
+    static __device__ __forceinline__ float zero() { return 0.f; }
+    static __device__ __forceinline__ void add(float &a, const float &b) { a += b; }
+    static __device__ __forceinline__ float shfl_xor(const float &a, int m) { return __shfl_xor(a, m, FAE_WAVE); }
+};
+
+// one row slice, or zero (and a status flag) when the slot is out of range
+template <typename V>
+__device__ __forceinline__ V fwd_load(const V *W, int slot, int n_hot, int ncols, int c, uint32_t *status)
+{
+    if ((unsigned)slot >= (unsigned)n_hot) {
+        fae_flag(status, FAE_STATUS_ERANGE);
+        return vec_ops<V>::zero();
+    }
+    return W[(int64_t)slot * ncols + c];
+}
+
+template <typename V, int LPR> __global__ __launch_bounds__(256) void fwd_group_kernel(FwdArgs a)
+{
+    constexpr int GPB = 256 / LPR;
+    const int z = fae_find_table(a.blk_start, a.n_tables, blockIdx.x);
+    const int bl = blockIdx.x - a.blk_start[z];
+    const int g = threadIdx.x / LPR, l = threadIdx.x % LPR;
+    const int64_t s = (int64_t)bl * GPB + g;
+    if (s >= a.n_samples)
+        return;
+    const int32_t *off = a.offsets[z];
+    const int32_t *slots = a.slots[z];
+    int beg = off ? off[s] : (int)s;
+    int end = off ? off[s + 1] : (int)s + 1;
+    if (beg < 0 || end > a.n_lookups[z] || beg > end) { // malformed CSR: never dereferenced
+        fae_flag(a.status, FAE_STATUS_ERANGE);
+        end = beg = 0;
+    }
+    const int ncols = a.dim / (int)(sizeof(V) / sizeof(float));
+    const V *W = (const V *)a.W[z];
+    const int n_hot = a.n_hot[z];
+    V *o = (V *)(a.out + s * a.out_stride + (int64_t)z * a.dim);
+    for (int c = l; c < ncols; c += LPR) {
+        V acc = vec_ops<V>::zero();
+        int j = beg;
+        for (; j + 4 <= end; j += 4) {
+            int s0 = slots[j], s1 = slots[j + 1], s2 = slots[j + 2], s3 = slots[j + 3];
+            V v0 = fwd_load(W, s0, n_hot, ncols, c, a.status);
+            V v1 = fwd_load(W, s1, n_hot, ncols, c, a.status);
+            V v2 = fwd_load(W, s2, n_hot, ncols, c, a.status);
+            V v3 = fwd_load(W, s3, n_hot, ncols, c, a.status);
+            vec_ops<V>::add(acc, v0);
+            vec_ops<V>::add(acc, v1);
+            vec_ops<V>::add(acc, v2);
+            vec_ops<V>::add(acc, v3);
+        }
+        for (; j < end; ++j) {
+            V v = fwd_load(W, slots[j], n_hot, ncols, c, a.status);
+            vec_ops<V>::add(acc, v);
+        }
+        o[c] = acc;
+    }
+}
+
+template <typename V, int LPR> __global__ __launch_bounds__(256) void fwd_wave_kernel(FwdArgs a)
+{
+    constexpr int G = FAE_WAVE / LPR; // lane groups per wave
+    constexpr int WPB = 256 / FAE_WAVE;
+    const int z = fae_find_table(a.blk_start, a.n_tables, blockIdx.x);
+    const int bl = blockIdx.x - a.blk_start[z];
+    const int w = threadIdx.x / FAE_WAVE, lane = threadIdx.x % FAE_WAVE;
+    const int g = lane / LPR, l = lane % LPR;
+    const int64_t s = (int64_t)bl * WPB + w;
+    if (s >= a.n_samples)
+        return;
+    const int32_t *off = a.offsets[z];
+    const int32_t *slots = a.slots[z];
+    int beg = off ? off[s] : (int)s;
+    int end = off ? off[s + 1] : (int)s + 1;
+    if (beg < 0 || end > a.n_lookups[z] || beg > end) { // malformed CSR: never dereferenced
+        fae_flag(a.status, FAE_STATUS_ERANGE);
+        end = beg = 0;
+    }
+    const int ncols = a.dim / (int)(sizeof(V) / sizeof(float));
+    const V *W = (const V *)a.W[z];
+    const int n_hot = a.n_hot[z];
+    V *o = (V *)(a.out + s * a.out_stride + (int64_t)z * a.dim);
+    for (int c0 = 0; c0 < ncols; c0 += LPR) {
+        const int c = c0 + l;
+        V acc = vec_ops<V>::zero();
+        if (c < ncols) {
+            int j = beg + g;
+            for (; j + 3 * G < end; j += 4 * G) {
+                int s0 = slots[j], s1 = slots[j + G], s2 = slots[j + 2 * G], s3 = slots[j + 3 * G];
+                V v0 = fwd_load(W, s0, n_hot, ncols, c, a.status);
+                V v1 = fwd_load(W, s1, n_hot, ncols, c, a.status);
+                V v2 = fwd_load(W, s2, n_hot, ncols, c, a.status);
+                V v3 = fwd_load(W, s3, n_hot, ncols, c, a.status);
+                vec_ops<V>::add(acc, v0);
+                vec_ops<V>::add(acc, v1);
+                vec_ops<V>::add(acc, v2);
+                vec_ops<V>::add(acc, v3);
+            }
+            for (; j < end; j += G) {
+                V v = fwd_load(W, slots[j], n_hot, ncols, c, a.status);
+                vec_ops<V>::add(acc, v);
+            }
+        }
+        // combine the lane groups (all 64 lanes take part in the shuffles)
+#pragma unroll
+        for (int m = LPR; m < FAE_WAVE; m <<= 1)
+            vec_ops<V>::add(acc, vec_ops<V>::shfl_xor(acc, m));
+        if (g == 0 && c < ncols)
+            o[c] = acc;
+    }
+}
+
+template <typename V, int LPR> static void fwd_launch(fae_ctx *ctx, const FwdArgs &a, bool wave, int total_blocks)
+{
+    if (wave)
+        hipLaunchKernelGGL((fwd_wave_kernel<V, LPR>), dim3(total_blocks), dim3(256), 0, ctx->stream, a);
+    else
+        hipLaunchKernelGGL((fwd_group_kernel<V, LPR>), dim3(total_blocks), dim3(256), 0, ctx->stream, a);
+}
+
+template <typename V> static void fwd_dispatch(fae_ctx *ctx, const FwdArgs &a, int lpr, bool wave, int total_blocks)
+{
+    switch (lpr) {
+    case 1: fwd_launch<V, 1>(ctx, a, wave, total_blocks); break;
+    case 2: fwd_launch<V, 2>(ctx, a, wave, total_blocks); break;
+    case 4: fwd_launch<V, 4>(ctx, a, wave, total_blocks); break;
+    case 8: fwd_launch<V, 8>(ctx, a, wave, total_blocks); break;
+    case 16: fwd_launch<V, 16>(ctx, a, wave, total_blocks); break;
+    case 32: fwd_launch<V, 32>(ctx, a, wave, total_blocks); break;
+    default: fwd_launch<V, 64>(ctx, a, wave, total_blocks); break;
+    }
+}
+
+extern "C" int32_t fae_embbag_fwd(fae_ctx *ctx, const fae_tables *hot_tables, const float *const *h_hotW,
+                                  const fae_batch *hot_batch, float *out, int64_t out_row_stride)
+{
+    int32_t rc = fae_check_tables(ctx, hot_tables, "fae_embbag_fwd");
+    if (rc != FAE_OK)
+        return rc;
+    rc = fae_check_batch(ctx, hot_tables, hot_batch, "fae_embbag_fwd");
+    if (rc != FAE_OK)
+        return rc;
+    const int nt = hot_tables->n_tables, dim = hot_tables->dim;
+    const int64_t S = hot_batch->n_samples;
+    if (S == 0)
+        return FAE_OK;
+    if (!h_hotW || !out || out_row_stride < (int64_t)nt * dim)
+        return fae_fail(ctx, FAE_EINVAL, "fae_embbag_fwd: null output/weights or out_row_stride < n_tables*dim");
+    FAE_HIP(ctx, hipSetDevice(ctx->device));
+
+    FwdArgs a;
+    memset(&a, 0, sizeof(a));
+    bool vec = (dim % 4 == 0) && (out_row_stride % 4 == 0) && (((uintptr_t)out) % 16 == 0);
+    int64_t total_lookups = 0;
+    bool any_csr = false;
+    for (int z = 0; z < nt; ++z) {
+        if (!h_hotW[z] && hot_tables->h_rows[z] > 0)
+            return fae_fail(ctx, FAE_EINVAL, "fae_embbag_fwd: null weights for table %d", z);
+        a.W[z] = h_hotW[z];
+        a.slots[z] = hot_batch->h_indices[z];
+        a.offsets[z] = hot_batch->h_offsets ? hot_batch->h_offsets[z] : nullptr;
+        a.n_hot[z] = (int32_t)hot_tables->h_rows[z];
+        a.n_lookups[z] = (int32_t)hot_batch->h_n_lookups[z];
+        if (((uintptr_t)h_hotW[z]) % 16 != 0)
+            vec = false;
+        total_lookups += hot_batch->h_n_lookups[z];
+        if (a.offsets[z])
+            any_csr = true;
+    }
+    const int ncols = vec ? dim / 4 : dim;
+    int lpr = 1;
+    while (lpr < ncols && lpr < 64)
+        lpr <<= 1;
+    // wave-per-bag pays once a bag keeps every lane group of the wave busy for a few rounds
+    const int groups = 64 / lpr;
+    double avg_len = (double)total_lookups / ((double)S * nt);
+    bool wave = any_csr && groups > 1 && avg_len >= 2.0 * groups;
+    if (ctx->opt_fwd == 1)
+        wave = false;
+    if (ctx->opt_fwd == 2)
+        wave = groups > 1;
+    const int bags_per_block = wave ? 4 : 256 / lpr;
+    const int64_t blk_per_table = (S + bags_per_block - 1) / bags_per_block;
+    if (blk_per_table * nt >= 2147483647LL)
+        return fae_fail(ctx, FAE_EINVAL, "fae_embbag_fwd: batch too large for one launch");
+    for (int z = 0; z <= nt; ++z)
+        a.blk_start[z] = (int32_t)(blk_per_table * z);
+    a.n_tables = nt;
+    a.dim = dim;
+    a.n_samples = (int32_t)S;
+    a.out_stride = out_row_stride;
+    a.out = out;
+    a.status = ctx->d_block;
+    const int total_blocks = (int)(blk_per_table * nt);
+    if (vec)
+        fwd_dispatch<float4>(ctx, a, lpr, wave, total_blocks);
+    else
+        fwd_dispatch<float>(ctx, a, lpr, wave, total_blocks);
+    FAE_LAUNCH_CHECK(ctx);
+    return FAE_OK;
+}

@@ -1,0 +1,160 @@
+// Internal declarations shared by the translation units of libfae (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stdio.h>
+#include <string.h>
+
+#include "../../include/fae.h"
+
+// ---------------------------------------------------------------------------------
+// context
+// ---------------------------------------------------------------------------------
+#define FAE_STATUS_ERANGE 1u
+#define FAE_STATUS_ENOSPC 2u
+
+// word offsets inside the 4 KiB device / pinned-host blocks
+#define FAE_BLK_STATUS 0
+#define FAE_BLK_SCALARS 64 // first word usable for scalar read-backs
+#define FAE_BLK_WORDS 1024
+
+struct fae_ctx {
+    int device;
+    hipStream_t stream;
+    uint32_t *d_block; // device, FAE_BLK_WORDS words
+    uint32_t *h_block; // pinned host mirror
+    int n_cu;
+    int64_t opt_profile; // 0 auto, 1 global atomics, 2 LDS-privatised
+    int64_t opt_fwd;     // 0 auto, 1 group-per-bag, 2 wave-per-bag
+    int64_t opt_sort;    // 0 auto, 1 global radix, 2 LDS per table
+    char err[512];
+};
+
+int32_t fae_fail(fae_ctx *ctx, int32_t code, const char *fmt, ...);
+// copy n words of the device block (from word `first`) to the pinned block and wait
+int32_t fae_readback(fae_ctx *ctx, int first, int n);
+// wait for the stream, fetch + clear the sticky status; maps it to an error code
+int32_t fae_sync_status(fae_ctx *ctx);
+int32_t fae_check_tables(fae_ctx *ctx, const fae_tables *t, const char *who);
+int32_t fae_check_batch(fae_ctx *ctx, const fae_tables *t, const fae_batch *b, const char *who);
+// data[0..n) -> exclusive prefix sums in place, data[n] = total (one workgroup; n+1 entries)
+int32_t fae_scan_i32(fae_ctx *ctx, int32_t *data, int64_t n);
+// fill n 32-bit words (a kernel, not a memset node: stays graph-capturable)
+int32_t fae_fill_u32(fae_ctx *ctx, void *p, int64_t n_words, uint32_t v);
+
+#define FAE_HIP(ctx, call)                                                                   \
+    do {                                                                                     \
+        hipError_t e_ = (call);                                                              \
+        if (e_ != hipSuccess)                                                                \
+            return fae_fail((ctx), FAE_EHIP, "%s: %s (%s:%d)", #call, hipGetErrorString(e_), \
+                            __FILE__, __LINE__);                                             \
+    } while (0)
+
+#define FAE_LAUNCH_CHECK(ctx) FAE_HIP(ctx, hipGetLastError())
+
+static inline size_t fae_align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// carve aligned sub-buffers out of a caller-provided workspace
+struct fae_carver {
+    char *base;
+    size_t used;
+    size_t cap;
+    bool ok;
+    fae_carver(void *ws, size_t bytes) : base((char *)ws), used(0), cap(bytes), ok(true) {}
+    template <typename T> T *take(size_t n)
+    {
+        size_t b = fae_align_up(n * sizeof(T), 256);
+        if (b == 0)
+            b = 256;
+        T *p = (T *)(base + used);
+        used += b;
+        if (used > cap || base == nullptr)
+            ok = false;
+        return p;
+    }
+};
+
+// ---------------------------------------------------------------------------------
+// device helpers (wave64)
+// ---------------------------------------------------------------------------------
+#ifdef __HIPCC__
+
+#define FAE_WAVE 64
+
+__device__ __forceinline__ int fae_lane() { return (int)__lane_id(); }
+
+__device__ __forceinline__ void fae_flag(uint32_t *status, uint32_t bit)
+{
+    // sticky status word; plain OR through a vector atomic, rare path
+    atomicOr(status + FAE_BLK_STATUS, bit);
+}
+
+// table that owns flat block index b, given exclusive prefix blk_start[0..nt]
+__device__ __forceinline__ int fae_find_table(const int32_t *blk_start, int nt, int b)
+{
+    int z = 0;
+    while (z + 1 < nt && b >= blk_start[z + 1])
+        ++z;
+    return z;
+}
+
+// inclusive scan across the 64 lanes of a wave
+__device__ __forceinline__ int fae_wave_incl_scan(int v)
+{
+    int lane = fae_lane();
+#pragma unroll
+    for (int d = 1; d < FAE_WAVE; d <<= 1) {
+        int n = __shfl_up(v, d, FAE_WAVE);
+        if (lane >= d)
+            v += n;
+    }
+    return v;
+}
+
+// exclusive scan across a block of BLOCK threads (BLOCK multiple of 64, <= 1024).
+// lds must hold BLOCK/64 + 1 ints.  Returns the exclusive prefix; *total = block sum.
+template <int BLOCK> __device__ __forceinline__ int fae_block_excl_scan(int v, int *lds, int *total)
+{
+    constexpr int NW = BLOCK / FAE_WAVE;
+    int lane = fae_lane(), w = threadIdx.x / FAE_WAVE;
+    int inc = fae_wave_incl_scan(v);
+    __syncthreads(); // lds may still be read from a previous call
+    if (lane == FAE_WAVE - 1)
+        lds[w] = inc;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int run = 0;
+        for (int i = 0; i < NW; ++i) {
+            int t = lds[i];
+            lds[i] = run;
+            run += t;
+        }
+        lds[NW] = run;
+    }
+    __syncthreads();
+    *total = lds[NW];
+    return lds[w] + inc - v;
+}
+
+// first position in sorted a[lo,hi) whose value is > key (upper bound)
+__device__ __forceinline__ int fae_upper_bound(const int32_t *a, int lo, int hi, int key)
+{
+    while (lo < hi) {
+        int mid = lo + ((hi - lo) >> 1);
+        if (a[mid] <= key)
+            lo = mid + 1;
+        else
+            hi = mid;
+    }
+    return lo;
+}
+
+// sample that owns lookup j in CSR offsets[0..n_samples] (offsets[s] <= j < offsets[s+1])
+__device__ __forceinline__ int fae_sample_of(const int32_t *offsets, int n_samples, int j)
+{
+    int s = fae_upper_bound(offsets, 0, n_samples + 1, j) - 1;
+    return s < 0 ? 0 : (s >= n_samples ? n_samples - 1 : s); // in range even for a malformed CSR
+}
+
+#endif // __HIPCC__

@@ -1,0 +1,57 @@
+// Small shared device utilities: in-place exclusive scan of an int32 array by one
+// workgroup, and a fill kernel (used instead of memset nodes so that every call
+// stays capturable in a HIP graph).
+#include "fae_internal.h"
+
+__global__ __launch_bounds__(1024) void fae_scan_kernel(int32_t *data, int64_t n)
+{
+    __shared__ int lds[1024 / FAE_WAVE + 1];
+    int carry = 0;
+    for (int64_t base = 0; base < n; base += 4096) {
+        const int64_t i0 = base + (int64_t)threadIdx.x * 4;
+        int v[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+            v[k] = (i0 + k < n) ? data[i0 + k] : 0;
+        int total;
+        int ex = fae_block_excl_scan<1024>(v[0] + v[1] + v[2] + v[3], lds, &total);
+        int run = carry + ex;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            if (i0 + k < n)
+                data[i0 + k] = run;
+            run += v[k];
+        }
+        carry += total;
+    }
+    if (threadIdx.x == 0)
+        data[n] = carry;
+}
+
+// data[0..n) -> exclusive prefix sums in place, data[n] = total (n+1 entries needed)
+int32_t fae_scan_i32(fae_ctx *ctx, int32_t *data, int64_t n)
+{
+    hipLaunchKernelGGL(fae_scan_kernel, dim3(1), dim3(1024), 0, ctx->stream, data, n);
+    FAE_LAUNCH_CHECK(ctx);
+    return FAE_OK;
+}
+
+__global__ __launch_bounds__(256) void fae_fill_kernel(uint32_t *p, int64_t n, uint32_t v)
+{
+    int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    for (; i < n; i += stride)
+        p[i] = v;
+}
+
+int32_t fae_fill_u32(fae_ctx *ctx, void *p, int64_t n_words, uint32_t v)
+{
+    if (n_words <= 0)
+        return FAE_OK;
+    int64_t blocks = (n_words + 255) / 256;
+    if (blocks > 65536)
+        blocks = 65536;
+    hipLaunchKernelGGL(fae_fill_kernel, dim3((unsigned)blocks), dim3(256), 0, ctx->stream, (uint32_t *)p, n_words, v);
+    FAE_LAUNCH_CHECK(ctx);
+    return FAE_OK;
+}

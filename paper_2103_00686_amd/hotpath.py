@@ -1,0 +1,145 @@
+"""Convenience driver around the C ABI: allocates device buffers and workspaces with
+torch (plumbing only) and calls the library stage by stage in the paper's order
+(Sec. 4: profile -> cutoff -> classify/replicate -> input classifier -> hot
+mini-batch forward / backward / SGD).  No arithmetic of the method happens here.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+from typing import List, Optional, Sequence
+
+import torch
+
+from . import binding as B
+
+
+@dataclass
+class HotBatch:
+    """A hot-only batch over the hot tables (slots instead of row ids)."""
+    n_samples: int
+    slots: List[torch.Tensor]
+    offsets: List[Optional[torch.Tensor]]
+    n_lookups: List[int]
+
+    def batch(self) -> B.Batch:
+        return B.Batch(self.n_samples, self.slots, self.offsets, self.n_lookups)
+
+    def slice(self, first: int, count: int) -> "HotBatch":
+        """Samples [first, first+count) as a batch of their own (offsets rebased to 0)."""
+        count = max(0, min(count, self.n_samples - first))
+        slots, offs, nl = [], [], []
+        for s, o in zip(self.slots, self.offsets):
+            if o is None:
+                slots.append(s[first:first + count])
+                offs.append(None)
+                nl.append(count)
+            else:
+                lo, hi = int(o[first]), int(o[first + count])
+                slots.append(s[lo:hi])
+                offs.append((o[first:first + count + 1] - lo).contiguous())
+                nl.append(hi - lo)
+        return HotBatch(count, slots, offs, nl)
+
+
+class HotPath:
+    def __init__(self, rows: Sequence[int], dim: int, device: int = 0):
+        self.dev = torch.device("cuda", device)
+        self.ctx = B.Context(device)
+        self.tables = B.Tables(list(rows), dim)
+        self.dim = dim
+        self.nt = len(rows)
+        self.counts: Optional[List[torch.Tensor]] = None
+        self.profiled_lookups = [0] * self.nt
+        self.profiled_samples = 0
+        self.remap = self.hot_ids = self.hotW = None
+        self.n_hot: List[int] = []
+        self._ws = {}
+
+    # -- plumbing -----------------------------------------------------------------
+    def _workspace(self, name: str, nbytes: int) -> torch.Tensor:
+        ws = self._ws.get(name)
+        if ws is None or ws.numel() < nbytes:
+            ws = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=self.dev)
+            self._ws[name] = ws
+        return ws
+
+    @property
+    def hot_tables(self) -> B.Tables:
+        return B.Tables(self.n_hot, self.dim)
+
+    # -- a1 -------------------------------------------------------------------------
+    def profile(self, chunk: B.Batch):
+        if self.counts is None:
+            self.counts = [torch.zeros(max(int(r), 1), dtype=torch.int32, device=self.dev) for r in self.tables.rows]
+        B.fae_profile(self.ctx, self.tables, chunk, self.counts)
+        self.profiled_samples += chunk.n_samples
+        for z in range(self.nt):
+            self.profiled_lookups[z] += int(chunk.n_lookups[z])
+
+    # -- a2 -------------------------------------------------------------------------
+    def choose_cutoff(self, budget_bytes: int, small_table_bytes: int = 1 << 20):
+        ws = self._workspace("cut", B.fae_choose_cutoff_workspace_bytes(self.tables))
+        return B.fae_choose_cutoff(self.ctx, self.tables, self.counts, self.profiled_lookups,
+                                   self.profiled_samples, budget_bytes, small_table_bytes, ws)
+
+    def count_hot(self, cutoff: Sequence[int]) -> List[int]:
+        ws = self._workspace("cut", B.fae_choose_cutoff_workspace_bytes(self.tables))
+        return B.fae_count_hot(self.ctx, self.tables, self.counts, cutoff, ws)
+
+    # -- a3 + a4 --------------------------------------------------------------------
+    def build(self, cutoff: Sequence[int], n_hot: Sequence[int], src_W: Optional[List[torch.Tensor]] = None,
+              seed: int = 0) -> List[int]:
+        self.remap = [torch.empty(max(int(r), 1), dtype=torch.int32, device=self.dev) for r in self.tables.rows]
+        self.hot_ids = [torch.empty(max(int(n), 1), dtype=torch.int32, device=self.dev) for n in n_hot]
+        self.hotW = [torch.empty((max(int(n), 1), self.dim), dtype=torch.float32, device=self.dev) for n in n_hot]
+        ws = self._workspace("build", B.fae_build_workspace_bytes(self.tables))
+        kind = B.FAE_SRC_DEVICE if src_W is not None else B.FAE_SRC_PROCEDURAL
+        got = B.fae_build_hot_tables(self.ctx, self.tables, self.counts, cutoff, kind, src_W, seed,
+                                     self.remap, self.hot_ids, self.hotW, [int(n) for n in n_hot], ws)
+        self.n_hot = [int(n) for n in got]
+        return self.n_hot
+
+    # -- a5 -------------------------------------------------------------------------
+    def partition(self, batch: B.Batch):
+        """Returns (hot_samples, cold_samples, HotBatch)."""
+        S = batch.n_samples
+        hot = torch.empty(max(S, 1), dtype=torch.int32, device=self.dev)
+        cold = torch.empty(max(S, 1), dtype=torch.int32, device=self.dev)
+        slots = [torch.empty(max(int(n), 1), dtype=torch.int32, device=self.dev) for n in batch.n_lookups]
+        hoff = [torch.empty(S + 1, dtype=torch.int32, device=self.dev) for _ in range(self.nt)]
+        ws = self._workspace("part", B.fae_partition_workspace_bytes(self.tables, S))
+        n_hot, nl = B.fae_partition_batch(self.ctx, self.tables, batch, self.remap, hot, cold, slots, hoff, ws)
+        hb = HotBatch(n_hot,
+                      [s[:n] for s, n in zip(slots, nl)],
+                      [None if o is None else h[:n_hot + 1] for o, h in zip(batch.offsets, hoff)],
+                      [int(n) for n in nl])
+        self.last_hoffsets = [h[:n_hot + 1] for h in hoff]
+        return hot[:n_hot], cold[:S - n_hot], hb
+
+    # -- a6 -------------------------------------------------------------------------
+    def forward(self, hb: HotBatch, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+        if out is None:
+            out = torch.empty((hb.n_samples, self.nt, self.dim), dtype=torch.float32, device=self.dev)
+        B.fae_embbag_fwd(self.ctx, self.hot_tables, self.hotW, hb.batch(), out, self.nt * self.dim)
+        return out
+
+    # -- a7 + a8 --------------------------------------------------------------------
+    def bwd_workspace(self, hb: HotBatch) -> torch.Tensor:
+        return self._workspace("bwd", B.fae_bwd_workspace_bytes(self.hot_tables, hb.n_samples, hb.n_lookups))
+
+    def backward_sgd(self, hb: HotBatch, gout: torch.Tensor, lr: float, debug: bool = False):
+        ws = self.bwd_workspace(hb)
+        if not debug:
+            B.fae_embbag_bwd_sgd(self.ctx, self.hot_tables, self.hotW, hb.batch(), gout, self.nt * self.dim, lr, ws)
+            return None
+        n = max(sum(hb.n_lookups), 1)
+        uniq = torch.empty(n, dtype=torch.int32, device=self.dev)
+        runlen = torch.empty(n, dtype=torch.int32, device=self.dev)
+        tstart = torch.zeros(self.nt + 1, dtype=torch.int32, device=self.dev)
+        B.fae_embbag_bwd_sgd(self.ctx, self.hot_tables, self.hotW, hb.batch(), gout, self.nt * self.dim, lr, ws,
+                             uniq, runlen, tstart)
+        ts = tstart.cpu().tolist()
+        return ([uniq[ts[z]:ts[z + 1]] for z in range(self.nt)], [runlen[ts[z]:ts[z + 1]] for z in range(self.nt)])
+
+    def sync(self):
+        B.fae_sync(self.ctx)

@@ -1,0 +1,196 @@
+"""Shared helpers of the GPU parity tests: run one workload through the HIP library
+(C ABI via the binding) and through the CPU oracle on the same seeded inputs and
+compare stage by stage.
+
+Tolerances.  Integer outputs (counts, cutoffs, remap, hot ids, sample lists, slots,
+offsets, distinct-slot lists, multiplicities) are compared bit-exactly.  fp32
+outputs must satisfy |gpu - ref| <= 1e-5 * sum|terms|, where ref is the oracle's
+fp64-accumulated result rounded once and the terms are the addends of the sum
+(pooled rows; |w_old| and lr*|g_j| for the update): "1e-5 relative" made well
+defined under cancellation.  Rows the step does not touch must be bit-identical.
+"""
+from __future__ import annotations
+
+from typing import List, Optional
+
+import numpy as np
+import torch
+
+from oracle import fae_oracle as O
+from paper_2103_00686_amd import binding as B
+from paper_2103_00686_amd import synth as S
+from paper_2103_00686_amd.hotpath import HotBatch, HotPath
+
+RTOL = 1e-5
+
+
+def to_dev(chunk: S.Chunk, dev) -> B.Batch:
+    return B.Batch(chunk.n_samples, [i.to(dev) for i in chunk.indices],
+                   [None if o is None else o.to(dev) for o in chunk.offsets], list(chunk.n_lookups))
+
+
+def np_idx(chunk: S.Chunk):
+    return ([i.cpu().numpy() for i in chunk.indices],
+            [None if o is None else o.cpu().numpy() for o in chunk.offsets])
+
+
+def assert_close_sum(gpu: np.ndarray, ref: np.ndarray, mag: np.ndarray, what: str):
+    err = np.abs(gpu.astype(np.float64) - ref.astype(np.float64))
+    bound = RTOL * mag + 1e-30
+    bad = err > bound
+    assert not bad.any(), f"{what}: {int(bad.sum())} of {bad.size} elements outside 1e-5*sum|terms| " \
+                          f"(worst ratio {float((err / bound).max()):.3g})"
+
+
+def oracle_profile(w: S.Workload, chunks: List[S.Chunk]):
+    cnts = [np.zeros(r, dtype=np.uint32) for r in w.rows]
+    for ch in chunks:
+        idx, _ = np_idx(ch)
+        for z in range(w.n_tables):
+            O.histogram(w.rows[z], idx[z], cnts[z])
+    return cnts
+
+
+def oracle_hot_rule(w: S.Workload, cnts, chunks):
+    """(cutoff[z], n_hot[z], c or None) by the workload's rule."""
+    if w.hot_rule == "cutoff":
+        H = [w.cutoff] * w.n_tables
+        return H, [O.count_hot(c, w.cutoff) for c in cnts], None
+    T = [sum(ch.n_lookups[z] for ch in chunks) for z in range(w.n_tables)]
+    n_prof = sum(ch.n_samples for ch in chunks)
+    c, H, nh = O.budget_cutoff(w.dim, cnts, T, n_prof, w.budget_bytes, w.small_table_bytes)
+    return [int(h) for h in H], [int(n) for n in nh], c
+
+
+class Pipeline:
+    """Both sides of one workload, kept in step."""
+
+    def __init__(self, w: S.Workload, dev, profile_chunks: int = 2, materialise: bool = False):
+        self.w, self.dev = w, dev
+        self.hp = HotPath(w.rows, w.dim, dev.index or 0)
+        per = -(-w.profile_samples // profile_chunks)
+        self.prof = [S.make_chunk(w, 0, i * per, min(per, w.profile_samples - i * per))
+                     for i in range(profile_chunks) if i * per < w.profile_samples]
+        self.materialise = materialise
+
+    # a1
+    def check_profile(self):
+        for ch in self.prof:
+            self.hp.profile(to_dev(ch, self.dev))
+        self.hp.sync()
+        self.cnts = oracle_profile(self.w, self.prof)
+        for z in range(self.w.n_tables):
+            got = self.hp.counts[z][:self.w.rows[z]].cpu().numpy().view(np.uint32)
+            assert np.array_equal(got, self.cnts[z]), f"histogram of table {z} differs"
+
+    # a2
+    def check_cutoff(self):
+        w = self.w
+        self.H, self.n_hot, c_ref = oracle_hot_rule(w, self.cnts, self.prof)
+        if w.hot_rule == "cutoff":
+            assert self.hp.count_hot(self.H) == self.n_hot
+        else:
+            c, H, nh = self.hp.choose_cutoff(w.budget_bytes, w.small_table_bytes)
+            assert (c, H, nh) == (c_ref, self.H, self.n_hot), f"cutoff: gpu {(c, H, nh)} vs oracle {(c_ref, self.H, self.n_hot)}"
+
+    # a3 + a4
+    def check_build(self):
+        w = self.w
+        src = [S.full_table(w, z).to(self.dev) for z in range(w.n_tables)] if self.materialise else None
+        got = self.hp.build(self.H, self.n_hot, src_W=src, seed=w.seed)
+        assert got == self.n_hot
+        self.remap, self.hot_ids, self.hotW = [], [], []
+        for z in range(w.n_tables):
+            remap, hot_ids = O.classify(self.cnts[z], self.H[z])
+            self.remap.append(remap)
+            self.hot_ids.append(hot_ids)
+            if self.materialise:
+                ref_w = O.gather_rows(src[z].cpu().numpy(), hot_ids)
+            else:
+                ref_w = O.w0_rows(w.seed, z, hot_ids.astype(np.int64), w.dim)
+            self.hotW.append(ref_w)
+            n = self.n_hot[z]
+            assert np.array_equal(self.hp.remap[z][:w.rows[z]].cpu().numpy(), remap), f"remap of table {z} differs"
+            assert np.array_equal(self.hp.hot_ids[z][:n].cpu().numpy(), hot_ids), f"hot ids of table {z} differ"
+            assert self.hp.hotW[z][:n].cpu().numpy().tobytes() == ref_w.tobytes(), f"hot weights of table {z} differ"
+
+    # a5
+    def check_partition(self, chunk: S.Chunk) -> HotBatch:
+        w = self.w
+        idx, off = np_idx(chunk)
+        hs, cs, slots, hoff = O.partition(w.rows, chunk.n_samples, idx, off, self.remap)
+        ghs, gcs, hb = self.hp.partition(to_dev(chunk, self.dev))
+        assert np.array_equal(ghs.cpu().numpy(), hs), "hot sample list differs"
+        assert np.array_equal(gcs.cpu().numpy(), cs), "cold sample list differs"
+        assert hb.n_samples == hs.size
+        for z in range(w.n_tables):
+            assert hb.n_lookups[z] == slots[z].size
+            assert np.array_equal(hb.slots[z].cpu().numpy(), slots[z]), f"slots of table {z} differ"
+            assert np.array_equal(self.hp.last_hoffsets[z].cpu().numpy(), hoff[z]), f"offsets of table {z} differ"
+        return hb
+
+    # a6
+    def check_forward(self, hb: HotBatch, exact_gather: bool = True):
+        """exact_gather: single-row bags must be bit-identical copies (only while the two
+        sides hold bit-identical weights, i.e. before the first update)."""
+        out = self.hp.forward(hb).cpu().numpy()
+        slots = [s.cpu().numpy() for s in hb.slots]
+        offs = [None if o is None else o.cpu().numpy() for o in hb.offsets]
+        ref, mag = O.embbag_fwd(self.hotW, hb.n_samples, slots, offs, want_mag=True)
+        assert_close_sum(out, ref, mag, "forward")
+        for z, o in enumerate(offs):   # single-row bags involve no arithmetic: bit-exact
+            if hb.n_samples == 0 or not exact_gather:
+                continue
+            if o is None:
+                assert out[:, z, :].tobytes() == ref[:, z, :].tobytes(), f"one-hot table {z} is not a bit-exact gather"
+            else:
+                one = np.diff(o) <= 1
+                assert out[one, z, :].tobytes() == ref[one, z, :].tobytes()
+        return out
+
+    # a7 + a8
+    def check_backward(self, hb: HotBatch, stream: int):
+        w = self.w
+        gout = S.upstream_grads(w, stream, hb.n_samples)
+        before = [x.clone() for x in self.hp.hotW]      # device-side snapshot of the library's own state
+        dbg = self.hp.backward_sgd(hb, gout.to(self.dev), w.lr, debug=True)
+        self.hp.sync()
+        slots = [s.cpu().numpy() for s in hb.slots]
+        offs = [None if o is None else o.cpu().numpy() for o in hb.offsets]
+        uniq, runlen, mag = O.embbag_bwd_sgd(self.hotW, hb.n_samples, slots, offs, gout.numpy(), w.lr, want_mag=True)
+        for z in range(w.n_tables):
+            assert np.array_equal(dbg[0][z].cpu().numpy(), uniq[z]), f"distinct slots of table {z} differ"
+            assert np.array_equal(dbg[1][z].cpu().numpy(), runlen[z]), f"multiplicities of table {z} differ"
+            got = self.hp.hotW[z][:self.n_hot[z]].cpu().numpy()
+            touched = np.zeros(self.n_hot[z], dtype=bool)
+            touched[uniq[z]] = True
+            prev = before[z][:self.n_hot[z]].cpu().numpy()
+            assert got[~touched].tobytes() == prev[~touched].tobytes(), f"untouched rows of table {z} changed"
+            if uniq[z].size:
+                assert_close_sum(got[uniq[z]], self.hotW[z][uniq[z]], mag[z], f"updated rows of table {z}")
+
+
+def hot_batches(p: Pipeline, n_batches: int, stream0: int = 10) -> List[HotBatch]:
+    """Hot-only mini-batches of the workload's batch size, the way the workload makes them:
+    conditional-hot draws for multi-hot workloads, partition of a mixed stream otherwise."""
+    w = p.w
+    out = []
+    if w.conditional_hot:
+        remap_t = [torch.from_numpy(r) for r in p.remap]
+        for b in range(n_batches):
+            ch = S.make_chunk(w, stream0 + b, 0, w.batch, hot_remap=remap_t)
+            hb = p.check_partition(ch)
+            assert hb.n_samples == w.batch
+            out.append(hb)
+        return out
+    need, first, got = n_batches * w.batch, 0, []
+    hb_all: Optional[HotBatch] = None
+    span = max(4 * need, 4096)
+    ch = S.make_chunk(w, stream0, first, span)
+    hb_all = p.check_partition(ch)
+    n_full = hb_all.n_samples // w.batch
+    for b in range(min(n_batches, n_full)):
+        out.append(hb_all.slice(b * w.batch, w.batch))
+    if not out:      # very selective hot set: use whatever is hot as one ragged batch
+        out.append(hb_all)
+    return out

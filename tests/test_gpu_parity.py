@@ -1,0 +1,238 @@
+"""GPU parity: the HIP library (through the C ABI) against the CPU oracle, element by
+element, on the five workloads at a scale the oracle finishes in seconds (several
+tiles plus ragged tails), and on the degenerate cases of the method."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import fae_oracle as O
+from paper_2103_00686_amd import binding as B
+from paper_2103_00686_amd import synth as S
+from paper_2103_00686_amd.hotpath import HotBatch, HotPath
+
+import fae_testlib as T
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def dev():
+    return torch.device("cuda", 0)
+
+
+@pytest.mark.parametrize("cfg_id", [1, 2, 3, 4, 5])
+@pytest.mark.parametrize("materialise", [False, True])
+def test_workload_end_to_end(dev, cfg_id, materialise):
+    if materialise and cfg_id in (3, 5):
+        pytest.skip("procedural weights only at this size")
+    w = S.workload(cfg_id, "test")
+    print(f"workload {w.name} materialise={materialise}", flush=True)
+    p = T.Pipeline(w, dev, profile_chunks=3, materialise=materialise)
+    p.check_profile()
+    p.check_cutoff()
+    p.check_build()
+    mixed = S.make_chunk(w, 5, 0, 3 * w.batch + 37)          # unconditioned: hot and cold inputs mixed
+    p.check_partition(mixed)
+    batches = T.hot_batches(p, 2)
+    p.check_forward(batches[0])
+    p.check_backward(batches[0], stream=20)
+    p.check_forward(batches[-1], exact_gather=False)           # sees the updated rows
+    p.check_backward(batches[-1], stream=21)                   # in-place state carried over
+    p.check_backward(batches[0], stream=22)
+
+
+@pytest.mark.parametrize("variant", [1, 2])
+def test_profile_variants_agree_with_oracle(dev, variant):
+    w = S.workload(2, "test")
+    p = T.Pipeline(w, dev, profile_chunks=2)
+    B.fae_set_option(p.hp.ctx, "profile_variant", variant)
+    p.check_profile()
+
+
+@pytest.mark.parametrize("variant", [1, 2])
+@pytest.mark.parametrize("dim", [4, 20, 32, 128, 6, 1, 260])
+def test_forward_backward_shapes(dev, variant, dim):
+    """Both lane mappings, vector and scalar paths, dims that are not powers of two, bags of
+    length 0..70 with repeats."""
+    rng = np.random.default_rng(dim)
+    n_hot, S_ = [700, 3, 1], 333
+    hp = HotPath(n_hot, dim, 0)
+    B.fae_set_option(hp.ctx, "fwd_variant", variant)
+    hp.n_hot = n_hot
+    Wref = [(rng.random((n, dim), dtype=np.float32) - 0.5) for n in n_hot]
+    hp.hotW = [torch.from_numpy(x).to(dev) for x in Wref]
+    slots, offs = [], []
+    for z, n in enumerate(n_hot):
+        if z == 1:
+            slots.append(rng.integers(0, n, S_).astype(np.int32))
+            offs.append(None)
+            continue
+        lens = rng.integers(0, 71, S_)
+        lens[rng.integers(0, S_, 40)] = 0
+        o = np.zeros(S_ + 1, dtype=np.int32)
+        o[1:] = np.cumsum(lens)
+        slots.append(rng.integers(0, n, int(o[-1])).astype(np.int32))
+        offs.append(o)
+    hb = HotBatch(S_, [torch.from_numpy(s).to(dev) for s in slots],
+                  [None if o is None else torch.from_numpy(o).to(dev) for o in offs], [s.size for s in slots])
+    out = hp.forward(hb).cpu().numpy()
+    ref, mag = O.embbag_fwd(Wref, S_, slots, offs, want_mag=True)
+    T.assert_close_sum(out, ref, mag, "forward")
+    gout = torch.from_numpy(rng.standard_normal((S_, 3, dim)).astype(np.float32))
+    dbg = hp.backward_sgd(hb, gout.to(dev), 0.05, debug=True)
+    hp.sync()
+    before = [x.copy() for x in Wref]
+    uniq, runlen, mg = O.embbag_bwd_sgd(Wref, S_, slots, offs, gout.numpy(), 0.05, want_mag=True)
+    for z in range(3):
+        assert np.array_equal(dbg[0][z].cpu().numpy(), uniq[z])
+        assert np.array_equal(dbg[1][z].cpu().numpy(), runlen[z])
+        got = hp.hotW[z].cpu().numpy()
+        T.assert_close_sum(got[uniq[z]], Wref[z][uniq[z]], mg[z], f"table {z}")
+        mask = np.ones(n_hot[z], bool)
+        mask[uniq[z]] = False
+        assert got[mask].tobytes() == before[z][mask].tobytes()
+
+
+def test_backward_long_runs_and_many_tiles(dev):
+    """One slot repeated tens of thousands of times (several pieces of a long run), runs just
+    below/above the long-run limit, more than one sort tile, three radix passes."""
+    rng = np.random.default_rng(7)
+    dim, n_hot, S_ = 64, 5_000_000, 50_000
+    slots = rng.integers(0, n_hot, S_).astype(np.int32)
+    slots[:20_000] = 4_999_999
+    slots[20_000:20_129] = 17          # 129 > limit
+    slots[20_129:20_257] = 18          # 128 = limit
+    slots[20_257:21_400] = 123_456     # one piece and a bit
+    slots = rng.permutation(slots)
+    lr = 0.01
+    rows = np.unique(slots)
+    hp = HotPath([n_hot], dim, 0)
+    hp.n_hot = [n_hot]
+    hp.hotW = [torch.zeros((n_hot, dim), dtype=torch.float32, device=dev)]
+    w_rows = (rng.random((rows.size, dim), dtype=np.float32) - 0.5)
+    hp.hotW[0][torch.from_numpy(rows.astype(np.int64)).to(dev)] = torch.from_numpy(w_rows).to(dev)
+    hb = HotBatch(S_, [torch.from_numpy(slots).to(dev)], [None], [S_])
+    gout = torch.from_numpy(rng.standard_normal((S_, 1, dim)).astype(np.float32))
+    dbg = hp.backward_sgd(hb, gout.to(dev), lr, debug=True)
+    hp.sync()
+    order, uniq, runlen = O.sort_runs(slots)
+    assert np.array_equal(dbg[0][0].cpu().numpy(), uniq) and np.array_equal(dbg[1][0].cpu().numpy(), runlen)
+    G, Ga = O.run_grads(order, O.bag_of(None, S_, S_), runlen, np.arange(uniq.size), gout.numpy(), 0)
+    ref = O.sgd_rows(w_rows, G, lr)
+    got = hp.hotW[0][torch.from_numpy(uniq.astype(np.int64)).to(dev)].cpu().numpy()
+    T.assert_close_sum(got, ref, np.abs(w_rows) + lr * Ga, "long runs")
+    # nothing else was written
+    total = float(hp.hotW[0].abs().sum(dtype=torch.float64))
+    assert abs(total - float(np.abs(got).astype(np.float64).sum())) < 1e-6 * max(total, 1.0)
+
+
+def test_integer_valued_case_is_bit_exact(dev):
+    """Integer weights/gradients and lr a power of two: every summation order is exact, so
+    forward and update must match the oracle bit for bit."""
+    rng = np.random.default_rng(11)
+    dim, n_hot, S_ = 16, 97, 900
+    W = rng.integers(-8, 9, (n_hot, dim)).astype(np.float32)
+    lens = rng.integers(0, 9, S_)
+    o = np.zeros(S_ + 1, dtype=np.int32)
+    o[1:] = np.cumsum(lens)
+    slots = rng.integers(0, n_hot, int(o[-1])).astype(np.int32)
+    hp = HotPath([n_hot], dim, 0)
+    hp.n_hot = [n_hot]
+    hp.hotW = [torch.from_numpy(W.copy()).to(dev)]
+    hb = HotBatch(S_, [torch.from_numpy(slots).to(dev)], [torch.from_numpy(o).to(dev)], [slots.size])
+    out = hp.forward(hb).cpu().numpy()
+    assert out.tobytes() == O.embbag_fwd([W], S_, [slots], [o]).tobytes()
+    gout = rng.integers(-4, 5, (S_, 1, dim)).astype(np.float32)
+    hp.backward_sgd(hb, torch.from_numpy(gout).to(dev), 0.125)
+    hp.sync()
+    O.embbag_bwd_sgd([W], S_, [slots], [o], gout, 0.125)
+    assert hp.hotW[0].cpu().numpy().tobytes() == W.tobytes()
+
+
+def test_degenerate_batches(dev):
+    w = S.workload(1)
+    p = T.Pipeline(w, dev, profile_chunks=1)
+    p.check_profile()
+    p.check_cutoff()
+    p.check_build()
+    # empty chunk
+    empty = S.Chunk(0, [torch.empty(0, dtype=torch.int32)], [None], [0])
+    hs, cs, hb = p.hp.partition(T.to_dev(empty, dev))
+    assert hs.numel() == 0 and cs.numel() == 0 and hb.n_samples == 0
+    assert p.hp.forward(hb).shape[0] == 0
+    p.hp.backward_sgd(hb, torch.empty((0, 1, w.dim), device=dev), w.lr)
+    # a chunk of only cold rows
+    cold_rows = np.nonzero(p.remap[0] < 0)[0][:300].astype(np.int32)
+    ch = S.Chunk(300, [torch.from_numpy(cold_rows)], [None], [300])
+    hb = p.check_partition(ch)
+    assert hb.n_samples == 0
+    # a chunk of only hot rows, every sample the same row
+    hot_row = int(p.hot_ids[0][0])
+    ch = S.Chunk(257, [torch.full((257,), hot_row, dtype=torch.int32)], [None], [257])
+    hb = p.check_partition(ch)
+    assert hb.n_samples == 257
+    p.check_forward(hb)
+    p.check_backward(hb, stream=3)
+    p.hp.sync()
+
+
+def test_cutoff_extremes(dev):
+    w = S.workload(2, "test")
+    p = T.Pipeline(w, dev, profile_chunks=1)
+    p.check_profile()
+    T_ = [ch for ch in p.prof]
+    lookups = [sum(ch.n_lookups[z] for ch in T_) for z in range(w.n_tables)]
+    n_prof = sum(ch.n_samples for ch in T_)
+    total = sum(w.rows) * w.dim * 4
+    small_total = sum(r for r in w.rows if r * w.dim * 4 < w.small_table_bytes) * w.dim * 4
+    for budget in (total, total - 1, small_total + 64 * 5, small_total):   # all hot ... nothing but small tables
+        ref = O.budget_cutoff(w.dim, p.cnts, lookups, n_prof, budget, w.small_table_bytes)
+        hp = p.hp
+        ws = hp._workspace("cut", B.fae_choose_cutoff_workspace_bytes(hp.tables))
+        got = B.fae_choose_cutoff(hp.ctx, hp.tables, hp.counts, lookups, n_prof, budget, w.small_table_bytes, ws)
+        assert got == (ref[0], [int(h) for h in ref[1]], [int(n) for n in ref[2]])
+    with pytest.raises(B.FaeError) as e:
+        B.fae_choose_cutoff(p.hp.ctx, p.hp.tables, p.hp.counts, lookups, n_prof, small_total - 1,
+                            w.small_table_bytes, ws)
+    assert e.value.code == B.FAE_ENOSPC
+
+
+def test_errors_are_reported_not_fatal(dev):
+    hp = HotPath([100], 8, 0)
+    bad = B.Batch(4, [torch.tensor([1, 2, 100, 3], dtype=torch.int32, device=dev)], [None], [4])
+    hp.profile(bad)
+    with pytest.raises(B.FaeError) as e:
+        hp.sync()
+    assert e.value.code == B.FAE_ERANGE
+    hp.sync()                                             # status was cleared
+    cnt = hp.counts[0].cpu().numpy()
+    assert cnt.sum() == 3 and cnt[[1, 2, 3]].tolist() == [1, 1, 1]
+    # slot out of range in forward / backward: skipped, flagged, nothing written out of bounds
+    hp.n_hot = [10]
+    hp.hotW = [torch.ones((10, 8), device=dev)]
+    hb = HotBatch(3, [torch.tensor([0, 10, -1], dtype=torch.int32, device=dev)], [None], [3])
+    out = hp.forward(hb)
+    with pytest.raises(B.FaeError):
+        hp.sync()
+    assert out.cpu()[0].eq(1).all() and out.cpu()[1:].eq(0).all()
+    hp.backward_sgd(hb, torch.ones((3, 1, 8), device=dev), 0.5)
+    with pytest.raises(B.FaeError):
+        hp.sync()
+    assert hp.hotW[0].cpu()[0].eq(0.5).all() and hp.hotW[0].cpu()[1:].eq(1).all()
+    # malformed CSR
+    off = torch.tensor([0, 3, 2, 4], dtype=torch.int32, device=dev)
+    hb = HotBatch(3, [torch.zeros(4, dtype=torch.int32, device=dev)], [off], [4])
+    hp.forward(hb)
+    with pytest.raises(B.FaeError):
+        hp.sync()
+    # capacity too small in build
+    hp2 = HotPath([1000], 4, 0)
+    hp2.profile(B.Batch(1000, [torch.arange(1000, dtype=torch.int32, device=dev)], [None], [1000]))
+    with pytest.raises(B.FaeError) as e:
+        hp2.build([1], [10], seed=1)
+    assert e.value.code == B.FAE_ENOSPC
+    # host-side argument checks
+    with pytest.raises(B.FaeError) as e:
+        B.fae_embbag_bwd_sgd(hp.ctx, hp.hot_tables, hp.hotW, HotBatch(3, [torch.zeros(3, dtype=torch.int32, device=dev)], [None], [3]).batch(),
+                             torch.ones((3, 1, 8), device=dev), 8, 0.1, torch.empty(256, dtype=torch.uint8, device=dev))
+    assert e.value.code == B.FAE_ENOSPC
