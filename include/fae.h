@@ -100,6 +100,31 @@ int32_t fae_sync(fae_ctx *ctx);
  * ("sort_variant", 0=auto 1=global radix 2=LDS per table). */
 int32_t fae_set_option(fae_ctx *ctx, const char *name, int64_t value);
 
+/* ---- per-kernel timing (measurement aid; off by default) ---------------------- */
+/* When enabled, every kernel launch of the listed classes is bracketed by HIP events
+ * on the context's stream.  fae_timing_read synchronises and returns, for one kernel
+ * class, the summed duration and the number of launches since the last reset. */
+#define FAE_K_FWD 0          /* pooled forward                                  */
+#define FAE_K_BWD_KEYS 1     /* (slot, sample) pairs                            */
+#define FAE_K_SORT_HIST 2    /* radix pass: per-tile digit histogram            */
+#define FAE_K_SORT_COLSCAN 3 /* radix pass: scan of digit counts over tiles     */
+#define FAE_K_SORT_SCATTER 4 /* radix pass: stable scatter                      */
+#define FAE_K_BWD_REDUCE 5   /* segment reduce + SGD                            */
+#define FAE_K_LONG_PREP 6    /* long runs: cut into pieces                      */
+#define FAE_K_LONG_PIECE 7   /* long runs: piece sums                           */
+#define FAE_K_LONG_FINAL 8   /* long runs: combine + SGD                        */
+#define FAE_K_LDS_SORT 9     /* per-table sort inside one workgroup's LDS       */
+#define FAE_K_FILL 10        /* fills / clears                                  */
+#define FAE_K_PROFILE 11     /* access histogram                                */
+#define FAE_K_PARTITION 12   /* input classifier kernels                        */
+#define FAE_K_BUILD 13       /* classify / scan / gather                        */
+#define FAE_K_OTHER 14
+#define FAE_K_COUNT 15
+int32_t fae_timing_enable(fae_ctx *ctx, int32_t on);
+int32_t fae_timing_reset(fae_ctx *ctx);
+int32_t fae_timing_read(fae_ctx *ctx, int32_t kernel_class, double *h_total_ms, int64_t *h_launches);
+const char *fae_kernel_name(int32_t kernel_class);
+
 /* ---- a1: Embedding Logger (Sec. 4.1.2) ------------------------------------- */
 /* counts_z[r] += number of lookups of `chunk` into row r of table z.  The caller
  * zeroes the counters before the first chunk; calls accumulate.  Asynchronous. */

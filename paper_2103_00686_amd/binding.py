@@ -21,6 +21,7 @@ FAE_SRC_DEVICE, FAE_SRC_PROCEDURAL = 0, 1
 
 EXPORTS = [
     "fae_create", "fae_destroy", "fae_last_error", "fae_version", "fae_sync", "fae_set_option",
+    "fae_timing_enable", "fae_timing_reset", "fae_timing_read", "fae_kernel_name",
     "fae_profile", "fae_choose_cutoff_workspace_bytes", "fae_choose_cutoff", "fae_count_hot",
     "fae_build_workspace_bytes", "fae_build_hot_tables", "fae_partition_workspace_bytes",
     "fae_partition_batch", "fae_embbag_fwd", "fae_bwd_workspace_bytes", "fae_embbag_bwd_sgd",
@@ -71,6 +72,7 @@ def load():
                  "fae_partition_workspace_bytes", "fae_bwd_workspace_bytes"):
         getattr(lib, name).restype = C.c_size_t
     lib.fae_destroy.restype = None
+    lib.fae_kernel_name.restype = C.c_char_p
     _lib = lib
     return lib
 
@@ -84,10 +86,14 @@ class Tables:
     dim: int
 
     def c(self):
-        rows = (C.c_int64 * len(self.rows))(*[int(r) for r in self.rows])
-        t = _Tables(len(self.rows), int(self.dim), rows)
-        t._keep = rows
-        return t
+        key = (tuple(int(r) for r in self.rows), int(self.dim))
+        cached = getattr(self, "_c", None)
+        if cached is None or cached[0] != key:     # marshal once; re-marshal if the shape changed
+            rows = (C.c_int64 * len(self.rows))(*key[0])
+            t = _Tables(len(self.rows), int(self.dim), rows)
+            t._keep = rows
+            self._c = (key, t)
+        return self._c[1]
 
 
 @dataclass
@@ -98,13 +104,16 @@ class Batch:
     n_lookups: Sequence[int]
 
     def c(self):
-        nt = len(self.indices)
-        idx = _ptrs(self.indices, torch.int32)
-        off = _ptrs(self.offsets, torch.int32) if any(o is not None for o in self.offsets) else None
-        nl = (C.c_int64 * nt)(*[int(n) for n in self.n_lookups])
-        b = _Batch(int(self.n_samples), idx, off, nl)
-        b._keep = (idx, off, nl)
-        return b
+        """Marshalled once per Batch object (the tensors must stay alive and in place)."""
+        if getattr(self, "_c", None) is None:
+            nt = len(self.indices)
+            idx = _ptrs(self.indices, torch.int32)
+            off = _ptrs(self.offsets, torch.int32) if any(o is not None for o in self.offsets) else None
+            nl = (C.c_int64 * nt)(*[int(n) for n in self.n_lookups])
+            b = _Batch(int(self.n_samples), idx, off, nl)
+            b._keep = (idx, off, nl)
+            self._c = b
+        return self._c
 
 
 def _ptrs(tensors: Sequence[Optional[torch.Tensor]], dtype):
@@ -171,6 +180,28 @@ def fae_sync(ctx: Context):
 
 def fae_set_option(ctx: Context, name: str, value: int):
     ctx.check(load().fae_set_option(ctx._h, name.encode(), C.c_int64(value)))
+
+
+FAE_K_COUNT = 15
+
+
+def fae_kernel_name(kernel_class: int) -> str:
+    return load().fae_kernel_name(C.c_int32(kernel_class)).decode()
+
+
+def fae_timing_enable(ctx: Context, on: bool):
+    ctx.check(load().fae_timing_enable(ctx._h, C.c_int32(1 if on else 0)))
+
+
+def fae_timing_reset(ctx: Context):
+    ctx.check(load().fae_timing_reset(ctx._h))
+
+
+def fae_timing_read(ctx: Context, kernel_class: int):
+    """(total milliseconds, launches) of one kernel class since the last reset."""
+    ms, n = C.c_double(0.0), C.c_int64(0)
+    ctx.check(load().fae_timing_read(ctx._h, C.c_int32(kernel_class), C.byref(ms), C.byref(n)))
+    return float(ms.value), int(n.value)
 
 
 def fae_profile(ctx: Context, tables: Tables, chunk: Batch, counts: List[torch.Tensor]):

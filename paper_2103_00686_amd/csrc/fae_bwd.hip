@@ -531,7 +531,11 @@ template <typename V, int LPR> void launch_reduce(fae_ctx *ctx, const BwdArgs &a
 }
 template <typename V, int LPR> void launch_long(fae_ctx *ctx, const BwdArgs &a, int piece_blocks, int final_blocks)
 {
-    hipLaunchKernelGGL((bwd_long_piece_kernel<V, LPR>), dim3(piece_blocks), dim3(256), 0, ctx->stream, a);
+    {
+        fae_ktimer kt(ctx, FAE_K_LONG_PIECE);
+        hipLaunchKernelGGL((bwd_long_piece_kernel<V, LPR>), dim3(piece_blocks), dim3(256), 0, ctx->stream, a);
+    }
+    fae_ktimer kt(ctx, FAE_K_LONG_FINAL);
     hipLaunchKernelGGL((bwd_long_final_kernel<V, LPR>), dim3(final_blocks), dim3(256), 0, ctx->stream, a);
 }
 
@@ -645,6 +649,7 @@ extern "C" int32_t fae_embbag_bwd_sgd(fae_ctx *ctx, const fae_tables *hot_tables
         a.blk_start[nt] = (int32_t)blocks;
         a.keys_in = w.keys[0];
         a.vals_in = w.vals[0];
+        fae_ktimer kt(ctx, FAE_K_BWD_KEYS);
         hipLaunchKernelGGL(bwd_keys_kernel, dim3((unsigned)blocks), dim3(256), 0, ctx->stream, a);
         FAE_LAUNCH_CHECK(ctx);
     }
@@ -662,12 +667,21 @@ extern "C" int32_t fae_embbag_bwd_sgd(fae_ctx *ctx, const fae_tables *hot_tables
         a.vals_in = w.vals[cur];
         a.keys_out = w.keys[cur ^ 1];
         a.vals_out = w.vals[cur ^ 1];
-        hipLaunchKernelGGL(sort_hist_kernel, dim3((unsigned)tiles), dim3(SORT_THREADS), 0, ctx->stream, a);
-        FAE_LAUNCH_CHECK(ctx);
-        hipLaunchKernelGGL(sort_colscan_kernel, dim3((unsigned)((nt * RADIX + 3) / 4)), dim3(256), 0, ctx->stream, a);
-        FAE_LAUNCH_CHECK(ctx);
-        hipLaunchKernelGGL(sort_scatter_kernel, dim3((unsigned)tiles), dim3(SORT_THREADS), 0, ctx->stream, a);
-        FAE_LAUNCH_CHECK(ctx);
+        {
+            fae_ktimer kt(ctx, FAE_K_SORT_HIST);
+            hipLaunchKernelGGL(sort_hist_kernel, dim3((unsigned)tiles), dim3(SORT_THREADS), 0, ctx->stream, a);
+            FAE_LAUNCH_CHECK(ctx);
+        }
+        {
+            fae_ktimer kt(ctx, FAE_K_SORT_COLSCAN);
+            hipLaunchKernelGGL(sort_colscan_kernel, dim3((unsigned)((nt * RADIX + 3) / 4)), dim3(256), 0, ctx->stream, a);
+            FAE_LAUNCH_CHECK(ctx);
+        }
+        {
+            fae_ktimer kt(ctx, FAE_K_SORT_SCATTER);
+            hipLaunchKernelGGL(sort_scatter_kernel, dim3((unsigned)tiles), dim3(SORT_THREADS), 0, ctx->stream, a);
+            FAE_LAUNCH_CHECK(ctx);
+        }
         cur ^= 1;
     }
     a.keys_in = w.keys[cur];
@@ -690,6 +704,7 @@ extern "C" int32_t fae_embbag_bwd_sgd(fae_ctx *ctx, const fae_tables *hot_tables
         }
         a.blk_start[nt] = (int32_t)blocks;
         const int nb = (int)blocks;
+        fae_ktimer kt(ctx, FAE_K_BWD_REDUCE);
 #define CALL_REDUCE(V, L) launch_reduce<V, L>(ctx, a, nb)
         if (vec) {
             BWD_LPR_SWITCH(float4, lpr, CALL_REDUCE)
@@ -704,8 +719,11 @@ extern "C" int32_t fae_embbag_bwd_sgd(fae_ctx *ctx, const fae_tables *hot_tables
         int prep_blocks = (int)((plan.long_cap + 255) / 256);
         if (prep_blocks > 256)
             prep_blocks = 256;
-        hipLaunchKernelGGL(bwd_long_prep_kernel, dim3(prep_blocks), dim3(256), 0, ctx->stream, a);
-        FAE_LAUNCH_CHECK(ctx);
+        {
+            fae_ktimer kt(ctx, FAE_K_LONG_PREP);
+            hipLaunchKernelGGL(bwd_long_prep_kernel, dim3(prep_blocks), dim3(256), 0, ctx->stream, a);
+            FAE_LAUNCH_CHECK(ctx);
+        }
         int piece_blocks = (int)(plan.piece_cap < 4 * ctx->n_cu ? plan.piece_cap : 4 * ctx->n_cu);
         int final_blocks = (int)((plan.long_cap + (256 / lpr) - 1) / (256 / lpr));
         if (final_blocks > 2 * ctx->n_cu)

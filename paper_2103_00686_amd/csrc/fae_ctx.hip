@@ -2,6 +2,8 @@
 #include <stdarg.h>
 #include <stdlib.h>
 
+#include <new>
+
 #include "fae_internal.h"
 
 int32_t fae_fail(fae_ctx *ctx, int32_t code, const char *fmt, ...)
@@ -30,29 +32,29 @@ extern "C" int32_t fae_create(fae_ctx **out, int32_t device, void *hip_stream)
     int n_dev = 0;
     if (hipGetDeviceCount(&n_dev) != hipSuccess || device < 0 || device >= n_dev)
         return FAE_EHIP;
-    fae_ctx *ctx = (fae_ctx *)calloc(1, sizeof(fae_ctx));
+    fae_ctx *ctx = new (std::nothrow) fae_ctx();
     if (!ctx)
         return FAE_ENOSPC;
     ctx->device = device;
     ctx->stream = (hipStream_t)hip_stream;
     if (hipSetDevice(device) != hipSuccess) {
-        free(ctx);
+        delete ctx;
         return FAE_EHIP;
     }
     hipDeviceProp_t prop;
     if (hipGetDeviceProperties(&prop, device) != hipSuccess) {
-        free(ctx);
+        delete ctx;
         return FAE_EHIP;
     }
     ctx->n_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
     if (hipMalloc((void **)&ctx->d_block, FAE_BLK_WORDS * sizeof(uint32_t)) != hipSuccess) {
-        free(ctx);
+        delete ctx;
         return FAE_EHIP;
     }
     if (hipHostMalloc((void **)&ctx->h_block, FAE_BLK_WORDS * sizeof(uint32_t), hipHostMallocDefault) !=
         hipSuccess) {
         (void)hipFree(ctx->d_block);
-        free(ctx);
+        delete ctx;
         return FAE_EHIP;
     }
     memset(ctx->h_block, 0, FAE_BLK_WORDS * sizeof(uint32_t));
@@ -61,7 +63,7 @@ extern "C" int32_t fae_create(fae_ctx **out, int32_t device, void *hip_stream)
     if (hipGetLastError() != hipSuccess || hipStreamSynchronize(ctx->stream) != hipSuccess) {
         (void)hipFree(ctx->d_block);
         (void)hipHostFree(ctx->h_block);
-        free(ctx);
+        delete ctx;
         return FAE_EHIP;
     }
     *out = ctx;
@@ -74,9 +76,107 @@ extern "C" void fae_destroy(fae_ctx *ctx)
         return;
     (void)hipSetDevice(ctx->device);
     (void)hipStreamSynchronize(ctx->stream);
+    for (const fae_timed_launch &t : ctx->timed) {
+        (void)hipEventDestroy(t.e0);
+        (void)hipEventDestroy(t.e1);
+    }
+    for (hipEvent_t e : ctx->event_pool)
+        (void)hipEventDestroy(e);
     (void)hipFree(ctx->d_block);
     (void)hipHostFree(ctx->h_block);
-    free(ctx);
+    delete ctx;
+}
+
+// ---------------------------------------------------------------------------------
+// per-kernel timing
+// ---------------------------------------------------------------------------------
+static hipEvent_t take_event(fae_ctx *c)
+{
+    if (!c->event_pool.empty()) {
+        hipEvent_t e = c->event_pool.back();
+        c->event_pool.pop_back();
+        return e;
+    }
+    hipEvent_t e = nullptr;
+    if (hipEventCreate(&e) != hipSuccess)
+        return nullptr;
+    return e;
+}
+
+fae_ktimer::fae_ktimer(fae_ctx *ctx, int id) : c(ctx), on(false)
+{
+    t.id = id;
+    t.e0 = t.e1 = nullptr;
+    if (!ctx || !ctx->timing)
+        return;
+    t.e0 = take_event(ctx);
+    t.e1 = take_event(ctx);
+    if (!t.e0 || !t.e1)
+        return;
+    on = hipEventRecord(t.e0, ctx->stream) == hipSuccess;
+}
+
+fae_ktimer::~fae_ktimer()
+{
+    if (!on)
+        return;
+    if (hipEventRecord(t.e1, c->stream) == hipSuccess)
+        c->timed.push_back(t);
+}
+
+static int32_t timing_collect(fae_ctx *ctx)
+{
+    FAE_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    for (const fae_timed_launch &t : ctx->timed) {
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, t.e0, t.e1) == hipSuccess) {
+            ctx->t_total_ms[t.id] += ms;
+            ctx->t_launches[t.id] += 1;
+        }
+        ctx->event_pool.push_back(t.e0);
+        ctx->event_pool.push_back(t.e1);
+    }
+    ctx->timed.clear();
+    return FAE_OK;
+}
+
+extern "C" int32_t fae_timing_enable(fae_ctx *ctx, int32_t on)
+{
+    if (!ctx)
+        return FAE_EINVAL;
+    int32_t rc = timing_collect(ctx);
+    ctx->timing = on != 0;
+    return rc;
+}
+
+extern "C" int32_t fae_timing_reset(fae_ctx *ctx)
+{
+    if (!ctx)
+        return FAE_EINVAL;
+    int32_t rc = timing_collect(ctx);
+    for (int i = 0; i < FAE_K_COUNT; ++i) {
+        ctx->t_total_ms[i] = 0.0;
+        ctx->t_launches[i] = 0;
+    }
+    return rc;
+}
+
+extern "C" int32_t fae_timing_read(fae_ctx *ctx, int32_t kernel_class, double *h_total_ms, int64_t *h_launches)
+{
+    if (!ctx || kernel_class < 0 || kernel_class >= FAE_K_COUNT || !h_total_ms || !h_launches)
+        return FAE_EINVAL;
+    int32_t rc = timing_collect(ctx);
+    *h_total_ms = ctx->t_total_ms[kernel_class];
+    *h_launches = ctx->t_launches[kernel_class];
+    return rc;
+}
+
+extern "C" const char *fae_kernel_name(int32_t k)
+{
+    static const char *names[FAE_K_COUNT] = {"fwd",        "bwd_keys",   "sort_hist",  "sort_colscan", "sort_scatter",
+                                             "bwd_reduce", "long_prep",  "long_piece", "long_final",   "lds_sort",
+                                             "fill",       "profile",    "partition",  "build",        "other"};
+    return (k >= 0 && k < FAE_K_COUNT) ? names[k] : "?";
 }
 
 extern "C" const char *fae_last_error(const fae_ctx *ctx) { return ctx ? ctx->err : "null context"; }

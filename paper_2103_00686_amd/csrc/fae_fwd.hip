@@ -236,6 +236,7 @@ extern "C" int32_t fae_embbag_fwd(fae_ctx *ctx, const fae_tables *hot_tables, co
     a.out = out;
     a.status = ctx->d_block;
     const int total_blocks = (int)(blk_per_table * nt);
+    fae_ktimer kt(ctx, FAE_K_FWD);
     if (vec)
         fwd_dispatch<float4>(ctx, a, lpr, wave, total_blocks);
     else

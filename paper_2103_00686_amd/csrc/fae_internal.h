@@ -6,6 +6,8 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <vector>
+
 #include "../../include/fae.h"
 
 // ---------------------------------------------------------------------------------
@@ -19,16 +21,36 @@
 #define FAE_BLK_SCALARS 64 // first word usable for scalar read-backs
 #define FAE_BLK_WORDS 1024
 
+struct fae_timed_launch {
+    int id;
+    hipEvent_t e0, e1;
+};
+
 struct fae_ctx {
-    int device;
-    hipStream_t stream;
-    uint32_t *d_block; // device, FAE_BLK_WORDS words
-    uint32_t *h_block; // pinned host mirror
-    int n_cu;
-    int64_t opt_profile; // 0 auto, 1 global atomics, 2 LDS-privatised
-    int64_t opt_fwd;     // 0 auto, 1 group-per-bag, 2 wave-per-bag
-    int64_t opt_sort;    // 0 auto, 1 global radix, 2 LDS per table
-    char err[512];
+    int device = 0;
+    hipStream_t stream = nullptr;
+    uint32_t *d_block = nullptr; // device, FAE_BLK_WORDS words
+    uint32_t *h_block = nullptr; // pinned host mirror
+    int n_cu = 256;
+    int64_t opt_profile = 0; // 0 auto, 1 global atomics, 2 LDS-privatised
+    int64_t opt_fwd = 0;     // 0 auto, 1 group-per-bag, 2 wave-per-bag
+    int64_t opt_sort = 0;    // 0 auto, 1 global radix, 2 LDS per table
+    char err[512] = {0};
+    // per-kernel timing
+    bool timing = false;
+    std::vector<fae_timed_launch> timed;  // launches recorded since the last read
+    std::vector<hipEvent_t> event_pool;   // events ready for reuse
+    double t_total_ms[FAE_K_COUNT] = {0};
+    int64_t t_launches[FAE_K_COUNT] = {0};
+};
+
+// Brackets the launches issued during its lifetime with two events (when timing is on).
+struct fae_ktimer {
+    fae_ctx *c;
+    fae_timed_launch t;
+    bool on;
+    fae_ktimer(fae_ctx *ctx, int id);
+    ~fae_ktimer();
 };
 
 int32_t fae_fail(fae_ctx *ctx, int32_t code, const char *fmt, ...);

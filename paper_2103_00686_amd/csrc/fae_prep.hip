@@ -165,6 +165,7 @@ extern "C" int32_t fae_profile(fae_ctx *ctx, const fae_tables *tables, const fae
     a.status = ctx->d_block;
     if (blocks >= 2147483647LL)
         return fae_fail(ctx, FAE_EINVAL, "fae_profile: chunk too large for one launch");
+    fae_ktimer kt(ctx, FAE_K_PROFILE);
     if (lds)
         hipLaunchKernelGGL(prof_lds_kernel, dim3((unsigned)blocks), dim3(PROF_THREADS), 0, ctx->stream, a);
     else
@@ -270,6 +271,7 @@ struct Window {
         if (rc != FAE_OK)
             return rc;
         if (blocks > 0) {
+            fae_ktimer kt(ctx, FAE_K_BUILD);
             hipLaunchKernelGGL(count_window_kernel, dim3((unsigned)blocks), dim3(256), 0, ctx->stream, a);
             FAE_LAUNCH_CHECK(ctx);
         }
@@ -658,6 +660,7 @@ extern "C" int32_t fae_build_hot_tables(fae_ctx *ctx, const fae_tables *tables, 
     if (rc != FAE_OK)
         return rc;
     if (tiles > 0) {
+        fae_ktimer kt(ctx, FAE_K_BUILD);
         hipLaunchKernelGGL(build_count_kernel, dim3((unsigned)tiles), dim3(256), 0, ctx->stream, a);
         FAE_LAUNCH_CHECK(ctx);
     }
@@ -665,6 +668,7 @@ extern "C" int32_t fae_build_hot_tables(fae_ctx *ctx, const fae_tables *tables, 
     if (rc != FAE_OK)
         return rc;
     if (tiles > 0) {
+        fae_ktimer kt(ctx, FAE_K_BUILD);
         hipLaunchKernelGGL(build_scatter_kernel, dim3((unsigned)tiles), dim3(256), 0, ctx->stream, a);
         FAE_LAUNCH_CHECK(ctx);
     }
@@ -705,6 +709,7 @@ extern "C" int32_t fae_build_hot_tables(fae_ctx *ctx, const fae_tables *tables, 
     if (blocks >= 2147483647LL)
         return fae_fail(ctx, FAE_EINVAL, "fae_build_hot_tables: hot set too large for one launch");
     if (blocks > 0) {
+        fae_ktimer kt(ctx, FAE_K_BUILD);
         if (vec)
             hipLaunchKernelGGL(gather_rows_kernel<float4>, dim3((unsigned)blocks), dim3(256), 0, ctx->stream, g);
         else

@@ -31,6 +31,7 @@ __global__ __launch_bounds__(1024) void fae_scan_kernel(int32_t *data, int64_t n
 // data[0..n) -> exclusive prefix sums in place, data[n] = total (n+1 entries needed)
 int32_t fae_scan_i32(fae_ctx *ctx, int32_t *data, int64_t n)
 {
+    fae_ktimer kt(ctx, FAE_K_OTHER);
     hipLaunchKernelGGL(fae_scan_kernel, dim3(1), dim3(1024), 0, ctx->stream, data, n);
     FAE_LAUNCH_CHECK(ctx);
     return FAE_OK;
@@ -51,6 +52,7 @@ int32_t fae_fill_u32(fae_ctx *ctx, void *p, int64_t n_words, uint32_t v)
     int64_t blocks = (n_words + 255) / 256;
     if (blocks > 65536)
         blocks = 65536;
+    fae_ktimer kt(ctx, FAE_K_FILL);
     hipLaunchKernelGGL(fae_fill_kernel, dim3((unsigned)blocks), dim3(256), 0, ctx->stream, (uint32_t *)p, n_words, v);
     FAE_LAUNCH_CHECK(ctx);
     return FAE_OK;

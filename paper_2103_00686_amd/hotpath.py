@@ -22,7 +22,9 @@ class HotBatch:
     n_lookups: List[int]
 
     def batch(self) -> B.Batch:
-        return B.Batch(self.n_samples, self.slots, self.offsets, self.n_lookups)
+        if getattr(self, "_b", None) is None:
+            self._b = B.Batch(self.n_samples, self.slots, self.offsets, self.n_lookups)
+        return self._b
 
     def slice(self, first: int, count: int) -> "HotBatch":
         """Samples [first, first+count) as a batch of their own (offsets rebased to 0)."""
@@ -65,7 +67,33 @@ class HotPath:
 
     @property
     def hot_tables(self) -> B.Tables:
-        return B.Tables(self.n_hot, self.dim)
+        t = getattr(self, "_hot_tables", None)
+        if t is None or list(t.rows) != list(self.n_hot):
+            t = self._hot_tables = B.Tables(list(self.n_hot), self.dim)
+        return t
+
+    def prepare_step(self, hb: HotBatch, gout: torch.Tensor, out: torch.Tensor, lr: float):
+        """Pre-marshalled forward + backward/SGD on one hot batch: returns a zero-argument
+        callable that only issues the two library calls (for tight training loops)."""
+        import ctypes as C
+        lib = B.load()
+        t, b = self.hot_tables.c(), hb.batch().c()
+        wptr = B._ptrs(self.hotW, torch.float32)
+        ws = self.bwd_workspace(hb)
+        stride = C.c_int64(self.nt * self.dim)
+        a_out, a_gout, a_ws = C.c_void_p(out.data_ptr()), C.c_void_p(gout.data_ptr()), C.c_void_p(ws.data_ptr())
+        n_ws, c_lr, h = C.c_size_t(ws.numel()), C.c_float(lr), self.ctx._h
+        tr, br = C.byref(t), C.byref(b)
+        keep = (t, b, wptr, ws, out, gout, hb)
+
+        def step():
+            rc = lib.fae_embbag_fwd(h, tr, wptr, br, a_out, stride)
+            if rc == 0:
+                rc = lib.fae_embbag_bwd_sgd(h, tr, wptr, br, a_gout, stride, c_lr, None, a_ws, n_ws)
+            if rc != 0:
+                self.ctx.check(rc)
+        step._keep = keep
+        return step
 
     # -- a1 -------------------------------------------------------------------------
     def profile(self, chunk: B.Batch):
