@@ -110,16 +110,14 @@ int32_t fae_set_option(fae_ctx *ctx, const char *name, int64_t value);
 #define FAE_K_SORT_COLSCAN 3 /* radix pass: scan of digit counts over tiles     */
 #define FAE_K_SORT_SCATTER 4 /* radix pass: stable scatter                      */
 #define FAE_K_BWD_REDUCE 5   /* segment reduce + SGD                            */
-#define FAE_K_LONG_PREP 6    /* long runs: cut into pieces                      */
-#define FAE_K_LONG_PIECE 7   /* long runs: piece sums                           */
-#define FAE_K_LONG_FINAL 8   /* long runs: combine + SGD                        */
-#define FAE_K_LDS_SORT 9     /* per-table sort inside one workgroup's LDS       */
-#define FAE_K_FILL 10        /* fills / clears                                  */
-#define FAE_K_PROFILE 11     /* access histogram                                */
-#define FAE_K_PARTITION 12   /* input classifier kernels                        */
-#define FAE_K_BUILD 13       /* classify / scan / gather                        */
-#define FAE_K_OTHER 14
-#define FAE_K_COUNT 15
+#define FAE_K_BWD_FIXUP 6    /* runs that cross span boundaries: combine + SGD  */
+#define FAE_K_LDS_SORT 7     /* per-table sort inside one workgroup's LDS       */
+#define FAE_K_FILL 8         /* fills / clears                                  */
+#define FAE_K_PROFILE 9      /* access histogram                                */
+#define FAE_K_PARTITION 10   /* input classifier kernels                        */
+#define FAE_K_BUILD 11       /* classify / scan / gather                        */
+#define FAE_K_OTHER 12
+#define FAE_K_COUNT 13
 int32_t fae_timing_enable(fae_ctx *ctx, int32_t on);
 int32_t fae_timing_reset(fae_ctx *ctx);
 int32_t fae_timing_read(fae_ctx *ctx, int32_t kernel_class, double *h_total_ms, int64_t *h_launches);

@@ -182,7 +182,7 @@ def fae_set_option(ctx: Context, name: str, value: int):
     ctx.check(load().fae_set_option(ctx._h, name.encode(), C.c_int64(value)))
 
 
-FAE_K_COUNT = 15
+FAE_K_COUNT = 13
 
 
 def fae_kernel_name(kernel_class: int) -> str:

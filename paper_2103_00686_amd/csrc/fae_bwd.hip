@@ -1,15 +1,19 @@
 // Hot mini-batch backward + sparse SGD (Sec. 2.2 "optimizer on embeddings", Sec. 6.2:
 // embedding update on the GPU for hot mini-batches).
 //
-//   1. keys      key = hot slot, value = sample id, per table segment
-//   2. sort      stable LSD radix sort of (key, value), segmented by table; only the
-//                bits a hot slot can occupy are sorted
-//   3. reduce    a lane group walks a chunk of the sorted lookups, sums the upstream
-//                gradient rows of each run of equal keys that STARTS in its chunk and
-//                applies w -= lr * G once per distinct row (no float atomics: every
-//                row has exactly one writer, sums follow sorted order)
-//   4. long runs runs longer than BWD_LONG are cut into pieces, summed by one
-//                workgroup per piece, then combined in piece order
+//   1. keys    key = hot slot, value = sample id, per table segment
+//   2. sort    stable LSD radix sort of (key, value), segmented by table; only the
+//              bits a hot slot can occupy are sorted
+//   3. reduce  one wave owns a span of the sorted lookups.  Its 64/LPR lane groups
+//              take consecutive lookups (LPR lanes x 16 B cover one gradient row), a
+//              segmented scan over the groups plus a carried (key, sum) pair sums
+//              each run of equal keys; a run that lies inside the span gets its SGD
+//              update w -= lr * G at once.  All gradient loads of a span are
+//              independent of the run structure, so they pipeline freely.
+//   4. fix-up  the first / last run of a span may continue in the neighbours: those
+//              sums go to a small scratch array and one lane group per crossing run
+//              adds them in span order and applies the update.
+// No float atomics: every row has exactly one writer and a fixed summation order.
 // Bandwidth bound: per lookup one gradient row is read, per distinct row one weight
 // row is read and written; the sort moves 16 B per lookup and pass.
 #include "fae_internal.h"
@@ -24,17 +28,10 @@
 #define RADIX_BITS 8
 #define RADIX (1 << RADIX_BITS)
 
-#define BWD_CHUNK 32    // sorted lookups per lane group in the reduce kernel
-#define BWD_LONG 128    // a run with more elements than this is handled by the long-run kernels
-#define BWD_PIECE 1024  // elements of a long run summed by one workgroup
+#define BWD_SPAN_MAX 256 // sorted lookups per wave in the reduce kernel (multiple of 64)
+#define BWD_SPAN_MIN 64
 #define DBG_TILE 2048
-
-struct LongRun {
-    int32_t z, key, start, end, piece_base, n_pieces;
-};
-struct Piece {
-    int32_t run, beg, end;
-};
+#define KEY_NONE 0x7fffffff // no carried run / element past the end of the span
 
 struct BwdArgs {
     float *W[FAE_MAX_TABLES];
@@ -54,11 +51,9 @@ struct BwdArgs {
     const float *gout;
     int64_t gout_stride;
     float lr;
-    LongRun *longq;
-    Piece *pieces;
-    float *partial;
-    int32_t *counters; // [0] long runs, [1] pieces
-    int32_t long_cap, piece_cap;
+    float *partial;    // [total spans][2][dim]: sums of a span's first / last run when they cross its border
+    int32_t span;      // lookups per wave in the reduce kernel
+    int32_t n_spans;   // total spans (blk_start then holds the span prefix per table)
     uint32_t *status;
     // debug outputs
     int32_t *dbg_uniq, *dbg_runlen, *dbg_table_start, *dbg_tile_sums, *dbg_rstart;
@@ -206,6 +201,207 @@ __global__ __launch_bounds__(SORT_THREADS) void sort_scatter_kernel(BwdArgs a)
 }
 
 // ---------------------------------------------------------------------------------
+// 2b. small tables: a table's list is sorted inside LDS by a few workgroups.
+// Each workgroup loads all keys of its table (64 KiB of LDS, left in place), takes the
+// keys whose top bits equal its part number (an ordered selection, so the input order
+// survives), and LSD-sorts that subset on the remaining low bits.  What moves is a
+// 16-bit permutation (position -> original lookup), ping-ponged between two 32 KiB
+// arrays.  A radix pass makes two sweeps over the permutation: a per-wave digit
+// histogram, then the same stable ranking as the global pass (wave-level match on
+// the digit, running per-wave offsets).  The parts of a table are disjoint key ranges,
+// so their outputs are laid end to end: part p starts after all keys of parts < p.
+// ---------------------------------------------------------------------------------
+#define LSORT_THREADS 1024
+#define LSORT_WAVES (LSORT_THREADS / FAE_WAVE)
+#define LSORT_MAX 16384
+#define LSORT_MAX_BLOCKS 1024
+
+struct LsortArgs {
+    const int32_t *slots[FAE_MAX_TABLES];
+    const int32_t *offsets[FAE_MAX_TABLES];
+    int32_t n_hot[FAE_MAX_TABLES];
+    int32_t seg_start[FAE_MAX_TABLES + 1];
+    int32_t blk_start[FAE_MAX_TABLES + 1]; // workgroups per table (0 for tables sorted elsewhere)
+    int32_t part_shift[FAE_MAX_TABLES];    // part of a key = key >> part_shift
+    int32_t n_tables;
+    int32_t n_samples;
+    int32_t *keys_out, *vals_out;
+    uint32_t *status;
+#ifdef FAE_PROBE
+    long long *probe;
+#endif
+};
+
+#ifdef FAE_PROBE
+#define PROBE(i) do { if (blockIdx.x == 0 && threadIdx.x == 0) a.probe[i] = wall_clock64(); } while (0)
+#else
+#define PROBE(i)
+#endif
+
+__global__ __launch_bounds__(LSORT_THREADS) void lds_sort_kernel(LsortArgs a)
+{
+    __shared__ int keyA[LSORT_MAX];
+    __shared__ unsigned short perm[2][LSORT_MAX];
+    __shared__ int wcnt[LSORT_WAVES][RADIX];
+    __shared__ int scan_lds[LSORT_THREADS / FAE_WAVE + 1];
+    const int z = fae_find_table(a.blk_start, a.n_tables, blockIdx.x);
+    const int part = blockIdx.x - a.blk_start[z];
+    const int pshift = a.part_shift[z];
+    const int n = a.seg_start[z + 1] - a.seg_start[z];
+    const int n_hot = a.n_hot[z];
+    const int32_t *off = a.offsets[z];
+    const int w = threadIdx.x / FAE_WAVE, lane = fae_lane();
+    const uint64_t lt_mask = (1ull << lane) - 1ull;
+
+    // load every key of the table; count the keys of lower parts (they precede this part's output)
+    bool bad = false;
+    int below = 0;
+    PROBE(0);
+    {
+        int kk[LSORT_MAX / LSORT_THREADS];
+#pragma unroll
+        for (int i = 0; i < LSORT_MAX / LSORT_THREADS; ++i) { // all loads in flight before the first use
+            const int e = threadIdx.x + i * LSORT_THREADS;
+            kk[i] = e < n ? a.slots[z][e] : 0;
+        }
+#pragma unroll
+        for (int i = 0; i < LSORT_MAX / LSORT_THREADS; ++i) {
+            const int e = threadIdx.x + i * LSORT_THREADS;
+            if (e < n) {
+                int k = kk[i];
+                if ((unsigned)k >= (unsigned)n_hot) {
+                    bad = true;
+                    k = n_hot; // behind every valid slot; never dereferenced
+                }
+                keyA[e] = k;
+                below += (k >> pshift) < part ? 1 : 0;
+            }
+        }
+    }
+    if (bad && part == 0)
+        fae_flag(a.status, FAE_STATUS_ERANGE);
+    // ordered selection of this part's lookups: wave w scans positions [w*per, (w+1)*per)
+    const int per = ((n + LSORT_THREADS - 1) / LSORT_THREADS) * FAE_WAVE;
+    __syncthreads();
+    int mine = 0;
+    for (int i = 0; i < per; i += FAE_WAVE) {
+        const int e = w * per + i + lane;
+        mine += (e < n && (keyA[e] >> pshift) == part) ? 1 : 0;
+    }
+    int n_below, n_sel;
+    (void)fae_block_excl_scan<LSORT_THREADS>(below, scan_lds, &n_below);
+    {
+        // per-wave totals -> exclusive prefix over the waves (scan over threads, read at lane 0)
+        const int ex = fae_block_excl_scan<LSORT_THREADS>(mine, scan_lds, &n_sel);
+        int run = __shfl(ex, 0, FAE_WAVE);
+        for (int i = 0; i < per; i += FAE_WAVE) {
+            const int e = w * per + i + lane;
+            const bool sel = e < n && (keyA[e] >> pshift) == part;
+            const uint64_t m = __ballot(sel);
+            if (sel)
+                perm[0][run + __popcll(m & lt_mask)] = (unsigned short)e;
+            run += __popcll(m);
+        }
+    }
+    __syncthreads();
+    PROBE(1);
+
+    // LSD passes over the bits below part_shift
+    const int passes = (pshift + RADIX_BITS - 1) / RADIX_BITS;
+    const int digit_bits = passes > 0 ? (pshift + passes - 1) / passes : RADIX_BITS;
+    const int mask = (1 << digit_bits) - 1;
+    const int rounds = (n_sel + LSORT_THREADS - 1) / LSORT_THREADS; // 64-element rounds per wave
+    const int wbase = w * rounds * FAE_WAVE + lane;
+    volatile int *my_cnt = wcnt[w];
+    int cur = 0;
+    for (int pass = 0; pass < passes; ++pass) {
+        const int shift = pass * digit_bits;
+        const unsigned short *src = perm[cur];
+        unsigned short *dst = perm[cur ^ 1];
+#pragma unroll
+        for (int i = 0; i < RADIX / FAE_WAVE; ++i)
+            wcnt[w][i * FAE_WAVE + lane] = 0;
+        __builtin_amdgcn_wave_barrier();
+        // sweep 1: digit histogram of the positions this wave owns
+        // (after the first pass neighbours mostly share a digit: one atomic per run of equal
+        // digits instead of 64 colliding ones)
+        for (int i = 0; i < rounds; ++i) {
+            const int pos = wbase + i * FAE_WAVE;
+            const bool valid = pos < n_sel;
+            const int d = valid ? (keyA[src[pos]] >> shift) & mask : -1;
+            const int dprev = __shfl_up(d, 1, FAE_WAVE);
+            const bool head = valid && (lane == 0 || dprev != d);
+            const uint64_t heads = __ballot(head) | ((__ballot(!valid) & (0 - __ballot(!valid))));
+            if (head) {
+                const uint64_t later = lane == FAE_WAVE - 1 ? 0ull : (heads >> (lane + 1));
+                const int len = later ? __builtin_ctzll(later) + 1 : FAE_WAVE - lane;
+                atomicAdd(&wcnt[w][d], len);
+            }
+        }
+        __syncthreads();
+        // digit t: counts -> exclusive prefix over (digit, wave)
+        int total = 0;
+        if (threadIdx.x < RADIX) {
+            for (int ww = 0; ww < LSORT_WAVES; ++ww) {
+                const int c = wcnt[ww][threadIdx.x];
+                wcnt[ww][threadIdx.x] = total;
+                total += c;
+            }
+        }
+        int all;
+        const int ex = fae_block_excl_scan<LSORT_THREADS>(total, scan_lds, &all);
+        if (threadIdx.x < RADIX) {
+            for (int ww = 0; ww < LSORT_WAVES; ++ww)
+                wcnt[ww][threadIdx.x] += ex;
+        }
+        __syncthreads();
+        // sweep 2: stable ranks, running offsets per wave and digit
+        for (int i = 0; i < rounds; ++i) {
+            const int pos = wbase + i * FAE_WAVE;
+            const bool valid = pos < n_sel;
+            const int e = valid ? src[pos] : 0;
+            const int d = valid ? (keyA[e] >> shift) & mask : 0;
+            uint64_t peers = __ballot(valid);
+#pragma unroll
+            for (int b = 0; b < RADIX_BITS; ++b) {
+                const bool bit = (d >> b) & 1;
+                const uint64_t m = __ballot(bit);
+                peers &= bit ? m : ~m;
+            }
+            const int r = __popcll(peers & lt_mask);
+            const int n_peers = __popcll(peers);
+            if (valid) {
+                const int old = my_cnt[d];
+                if (r == 0)
+                    my_cnt[d] = old + n_peers;
+                dst[old + r] = (unsigned short)e;
+            }
+            __builtin_amdgcn_wave_barrier();
+        }
+        __syncthreads();
+        cur ^= 1;
+    }
+    PROBE(2);
+    const int out0 = a.seg_start[z] + n_below;
+    const unsigned short *fin = perm[cur];
+    bad = false;
+    for (int pos = threadIdx.x; pos < n_sel; pos += LSORT_THREADS) {
+        const int e = fin[pos];
+        int s = e;
+        if (off) {
+            s = fae_sample_of(off, a.n_samples, e);
+            if (off[s] > e || off[s + 1] <= e)
+                bad = true; // malformed CSR
+        }
+        a.keys_out[out0 + pos] = keyA[e];
+        a.vals_out[out0 + pos] = s;
+    }
+    PROBE(3);
+    if (bad)
+        fae_flag(a.status, FAE_STATUS_ERANGE);
+}
+
+// ---------------------------------------------------------------------------------
 // 3. segment reduce + SGD for runs that start inside a chunk
 // ---------------------------------------------------------------------------------
 template <typename V> struct bwd_vec;
@@ -229,169 +425,178 @@ template <> struct bwd_vec<float> {
     static __device__ __forceinline__ float sgd(const float &w, const float &g, float lr) { return w - lr * g; }
 };
 
+template <typename V> __device__ __forceinline__ V bwd_shfl_up(const V &v, int d);
+template <> __device__ __forceinline__ float4 bwd_shfl_up<float4>(const float4 &v, int d)
+{
+    return make_float4(__shfl_up(v.x, d, FAE_WAVE), __shfl_up(v.y, d, FAE_WAVE), __shfl_up(v.z, d, FAE_WAVE),
+                       __shfl_up(v.w, d, FAE_WAVE));
+}
+template <> __device__ __forceinline__ float bwd_shfl_up<float>(const float &v, int d) { return __shfl_up(v, d, FAE_WAVE); }
+template <typename V> __device__ __forceinline__ V bwd_shfl(const V &v, int src);
+template <> __device__ __forceinline__ float4 bwd_shfl<float4>(const float4 &v, int src)
+{
+    return make_float4(__shfl(v.x, src, FAE_WAVE), __shfl(v.y, src, FAE_WAVE), __shfl(v.z, src, FAE_WAVE),
+                       __shfl(v.w, src, FAE_WAVE));
+}
+template <> __device__ __forceinline__ float bwd_shfl<float>(const float &v, int src) { return __shfl(v, src, FAE_WAVE); }
+
+// What a span knows about its borders (same predicate in the reduce and the fix-up kernel).
+struct SpanInfo {
+    int z, seg0, seg1, pos0, pos1, first_key, last_key, local;
+    bool head_open, tail_open;
+};
+
+__device__ __forceinline__ SpanInfo bwd_span_info(const BwdArgs &a, int sid)
+{
+    SpanInfo s;
+    s.z = fae_find_table(a.blk_start, a.n_tables, sid);
+    s.local = sid - a.blk_start[s.z];
+    s.seg0 = a.seg_start[s.z];
+    s.seg1 = a.seg_start[s.z + 1];
+    s.pos0 = s.seg0 + s.local * a.span;
+    s.pos1 = s.pos0 + a.span < s.seg1 ? s.pos0 + a.span : s.seg1;
+    // four independent loads (indices clamped into the segment), no dependent branches
+    s.first_key = a.keys_in[s.pos0];
+    s.last_key = a.keys_in[s.pos1 - 1];
+    const int before = a.keys_in[s.pos0 > s.seg0 ? s.pos0 - 1 : s.seg0];
+    const int after = a.keys_in[s.pos1 < s.seg1 ? s.pos1 : s.seg1 - 1];
+    s.head_open = s.pos0 > s.seg0 && before == s.first_key;
+    s.tail_open = s.pos1 < s.seg1 && after == s.last_key;
+    return s;
+}
+
 template <typename V, int LPR> __global__ __launch_bounds__(256) void bwd_reduce_kernel(BwdArgs a)
 {
-    constexpr int GPB = 256 / LPR;
+    constexpr int G = FAE_WAVE / LPR;              // lane groups = gradient rows per step
     constexpr int VW = sizeof(V) / sizeof(float);
-    const int z = fae_find_table(a.blk_start, a.n_tables, blockIdx.x);
-    const int bl = blockIdx.x - a.blk_start[z];
-    const int g = threadIdx.x / LPR, l = threadIdx.x % LPR;
-    const int seg0 = a.seg_start[z], seg1 = a.seg_start[z + 1];
-    const int64_t chunk = (int64_t)bl * GPB + g;
-    const int64_t pos0_64 = seg0 + chunk * BWD_CHUNK;
-    if (pos0_64 >= seg1)
+    constexpr int STEPS = FAE_WAVE / G;            // steps per tile of 64 lookups
+    constexpr int UN = STEPS < 4 ? STEPS : 4;      // steps whose loads are issued together
+    const int sid = blockIdx.x * (256 / FAE_WAVE) + threadIdx.x / FAE_WAVE;
+    if (sid >= a.n_spans)
         return;
-    const int pos0 = (int)pos0_64;
-    const int pos1 = pos0 + BWD_CHUNK < seg1 ? pos0 + BWD_CHUNK : seg1;
+    const SpanInfo sp = bwd_span_info(a, sid);
+    const int lane = fae_lane(), g = lane / LPR, l = lane % LPR;
     const int ncols = a.dim / VW;
-    const int n_hot = a.n_hot[z];
-    const int32_t *keys = a.keys_in, *vals = a.vals_in;
-    V *W = (V *)a.W[z];
-    const float *gbase = a.gout + (int64_t)z * a.dim;
+    const int n_hot = a.n_hot[sp.z];
+    V *W = (V *)a.W[sp.z];
+    const float *gbase = a.gout + (int64_t)sp.z * a.dim;
+    V *part = (V *)(a.partial + (int64_t)sid * 2 * a.dim);
+
     for (int c0 = 0; c0 < ncols; c0 += LPR) {
         const int c = c0 + l;
         const bool active = c < ncols;
-        int p = pos0;
-        if (p > seg0) { // a run that began in an earlier chunk belongs to that chunk
-            const int kprev = keys[p - 1];
-            while (p < pos1 && keys[p] == kprev)
-                ++p;
-        }
-        while (p < pos1) {
-            const int k = keys[p];
-            if (k >= n_hot) { // invalid slots (flagged when the keys were built) end the segment
-                p = pos1;
-                break;
-            }
-            if (p + BWD_LONG < seg1 && keys[p + BWD_LONG] == k) {
-                if (l == 0 && c0 == 0) {
-                    int q = atomicAdd(&a.counters[0], 1);
-                    if (q < a.long_cap) {
-                        LongRun r;
-                        r.z = z;
-                        r.key = k;
-                        r.start = p;
-                        r.end = 0;
-                        r.piece_base = 0;
-                        r.n_pieces = 0;
-                        a.longq[q] = r;
+        int ck = KEY_NONE; // key of the run still open at the end of the previous step
+        V cv = bwd_vec<V>::zero();
+        for (int t0 = sp.pos0; t0 < sp.pos1; t0 += FAE_WAVE) {
+            const int p = t0 + lane;
+            const int kreg = p < sp.pos1 ? a.keys_in[p] : KEY_NONE;
+            const int sreg = p < sp.pos1 ? a.vals_in[p] : 0;
+            // key that follows each lookup; the span's last lookup always closes its run here
+            int kafter = __shfl_down(kreg, 1, FAE_WAVE);
+            if (lane == FAE_WAVE - 1)
+                kafter = t0 + FAE_WAVE < sp.pos1 ? a.keys_in[t0 + FAE_WAVE] : KEY_NONE;
+            if (p == sp.pos1 - 1)
+                kafter = KEY_NONE;
+            // where the finished run of lookup p goes: 0 nowhere (not the last of its run, or an
+            // invalid slot), 1 SGD on its row, 2 / 3 the span's head / tail scratch row
+            int dreg = 0;
+            if (p < sp.pos1 && kafter != kreg && kreg < n_hot)
+                dreg = (sp.head_open && kreg == sp.first_key) ? 2 : ((sp.tail_open && kreg == sp.last_key) ? 3 : 1);
+            for (int i0 = 0; i0 < STEPS; i0 += UN) {
+                if (t0 + i0 * G >= sp.pos1)
+                    break;
+                int kk[UN], dd[UN];
+                V vv[UN], ww[UN];
+#pragma unroll
+                for (int u = 0; u < UN; ++u) { // every load of the batch is issued before the first use
+                    const int e = (i0 + u) * G + g;
+                    kk[u] = __shfl(kreg, e, FAE_WAVE);
+                    dd[u] = __shfl(dreg, e, FAE_WAVE);
+                    const int s = __shfl(sreg, e, FAE_WAVE);
+                    vv[u] = (active && kk[u] != KEY_NONE) ? ((const V *)(gbase + (int64_t)s * a.gout_stride))[c]
+                                                         : bwd_vec<V>::zero();
+                    ww[u] = (active && dd[u] == 1) ? W[(int64_t)kk[u] * ncols + c] : bwd_vec<V>::zero();
+                }
+#pragma unroll
+                for (int u = 0; u < UN; ++u) {
+                    const int kg = kk[u];
+                    V vg = vv[u];
+                    // inclusive segmented scan over the lane groups (equal keys are adjacent)
+#pragma unroll
+                    for (int d = 1; d < G; d <<= 1) {
+                        const int kp = __shfl_up(kg, d * LPR, FAE_WAVE);
+                        const V vp = bwd_shfl_up<V>(vg, d * LPR);
+                        if (g >= d && kp == kg)
+                            bwd_vec<V>::add(vg, vp);
                     }
+                    if (kg == ck)
+                        bwd_vec<V>::add(vg, cv); // the run was already open before this step
+                    if (active) {
+                        if (dd[u] == 1)
+                            W[(int64_t)kg * ncols + c] = bwd_vec<V>::sgd(ww[u], vg, a.lr);
+                        else if (dd[u] == 2)
+                            part[c] = vg;
+                        else if (dd[u] == 3)
+                            part[ncols + c] = vg;
+                    }
+                    // the last group's run stays open unless it just ended
+                    const int last_k = __shfl(kg, (G - 1) * LPR + l, FAE_WAVE);
+                    const int last_d = __shfl(dd[u], (G - 1) * LPR + l, FAE_WAVE);
+                    cv = bwd_shfl<V>(vg, (G - 1) * LPR + l);
+                    ck = (last_d != 0 || last_k >= n_hot) ? KEY_NONE : last_k;
                 }
-                ++p;
-                while (p < pos1 && keys[p] == k)
-                    ++p;
-                continue;
             }
-            V acc = bwd_vec<V>::zero();
-            int q = p;
-            do {
-                const int s = vals[q];
-                if (active)
-                    bwd_vec<V>::add(acc, ((const V *)(gbase + (int64_t)s * a.gout_stride))[c]);
-                ++q;
-            } while (q < seg1 && keys[q] == k);
-            if (active) {
-                V *wp = W + (int64_t)k * ncols + c;
-                *wp = bwd_vec<V>::sgd(*wp, acc, a.lr);
-            }
-            p = q;
         }
     }
 }
 
-// ---------------------------------------------------------------------------------
-// 4. long runs
-// ---------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void bwd_long_prep_kernel(BwdArgs a)
+// one wave per span: if a run starts in this span and continues past its end, add the
+// pieces (this span's tail, the following spans' heads) and apply the update.  The lanes
+// find the extent of the run together (64 following spans per ballot) and the lane groups
+// add alternate heads; the order of the additions is fixed by the span numbers.
+template <typename V, int LPR> __global__ __launch_bounds__(256) void bwd_fixup_kernel(BwdArgs a)
 {
-    int n_long = a.counters[0];
-    if (n_long > a.long_cap)
-        n_long = a.long_cap;
-    for (int q = blockIdx.x * 256 + threadIdx.x; q < n_long; q += gridDim.x * 256) {
-        LongRun r = a.longq[q];
-        const int seg1 = a.seg_start[r.z + 1];
-        r.end = fae_upper_bound(a.keys_in, r.start, seg1, r.key);
-        r.n_pieces = (r.end - r.start + BWD_PIECE - 1) / BWD_PIECE;
-        r.piece_base = atomicAdd(&a.counters[1], r.n_pieces);
-        for (int i = 0; i < r.n_pieces; ++i) {
-            if (r.piece_base + i < a.piece_cap) {
-                Piece pc;
-                pc.run = q;
-                pc.beg = r.start + i * BWD_PIECE;
-                pc.end = pc.beg + BWD_PIECE < r.end ? pc.beg + BWD_PIECE : r.end;
-                a.pieces[r.piece_base + i] = pc;
-            }
-        }
-        a.longq[q] = r;
-    }
-}
-
-// one workgroup per piece: lane groups take alternate rows, then are summed in group order
-template <typename V, int LPR> __global__ __launch_bounds__(256) void bwd_long_piece_kernel(BwdArgs a)
-{
-    constexpr int G = 256 / LPR;
+    constexpr int G = FAE_WAVE / LPR;
     constexpr int VW = sizeof(V) / sizeof(float);
-    __shared__ V red[256];
-    int n_pieces = a.counters[1];
-    if (n_pieces > a.piece_cap)
-        n_pieces = a.piece_cap;
-    const int g = threadIdx.x / LPR, l = threadIdx.x % LPR;
-    const int ncols = a.dim / VW;
-    for (int pi = blockIdx.x; pi < n_pieces; pi += gridDim.x) {
-        const Piece pc = a.pieces[pi];
-        const int z = a.longq[pc.run].z;
-        const float *gbase = a.gout + (int64_t)z * a.dim;
-        for (int c0 = 0; c0 < ncols; c0 += LPR) {
-            const int c = c0 + l;
-            V acc = bwd_vec<V>::zero();
-            if (c < ncols) {
-                int q = pc.beg + g;
-                for (; q + 3 * G < pc.end; q += 4 * G) {
-                    const int s0 = a.vals_in[q], s1 = a.vals_in[q + G], s2 = a.vals_in[q + 2 * G], s3 = a.vals_in[q + 3 * G];
-                    const V v0 = ((const V *)(gbase + (int64_t)s0 * a.gout_stride))[c];
-                    const V v1 = ((const V *)(gbase + (int64_t)s1 * a.gout_stride))[c];
-                    const V v2 = ((const V *)(gbase + (int64_t)s2 * a.gout_stride))[c];
-                    const V v3 = ((const V *)(gbase + (int64_t)s3 * a.gout_stride))[c];
-                    bwd_vec<V>::add(acc, v0);
-                    bwd_vec<V>::add(acc, v1);
-                    bwd_vec<V>::add(acc, v2);
-                    bwd_vec<V>::add(acc, v3);
-                }
-                for (; q < pc.end; q += G)
-                    bwd_vec<V>::add(acc, ((const V *)(gbase + (int64_t)a.vals_in[q] * a.gout_stride))[c]);
-            }
-            __syncthreads(); // red may still be read from the previous column block / piece
-            red[threadIdx.x] = acc;
-            __syncthreads();
-            if (g == 0 && c < ncols) {
-                V sum = red[l];
-                for (int gg = 1; gg < G; ++gg)
-                    bwd_vec<V>::add(sum, red[gg * LPR + l]);
-                ((V *)(a.partial + (int64_t)pi * a.dim))[c] = sum;
-            }
-        }
+    const int sid = blockIdx.x * (256 / FAE_WAVE) + threadIdx.x / FAE_WAVE;
+    if (sid >= a.n_spans)
+        return;
+    const SpanInfo sp = bwd_span_info(a, sid);
+    if (!sp.tail_open || (sp.head_open && sp.first_key == sp.last_key))
+        return; // nothing crosses the end, or the run began in an earlier span
+    const int k = sp.last_key;
+    if (k >= a.n_hot[sp.z])
+        return;
+    const int lane = fae_lane(), g = lane / LPR, l = lane % LPR;
+    const int spans_z = a.blk_start[sp.z + 1] - a.blk_start[sp.z];
+    // following spans that begin with the same key continue the run (keys are sorted)
+    int n_follow = 0;
+    for (int base = sp.local + 1; base < spans_z; base += FAE_WAVE) {
+        const int j = base + lane;
+        const bool same = j < spans_z && a.keys_in[sp.seg0 + j * a.span] == k;
+        const uint64_t m = __ballot(same);
+        const int run = m == ~0ull ? FAE_WAVE : __builtin_ctzll(~m);
+        n_follow += run;
+        if (run < FAE_WAVE)
+            break;
     }
-}
-
-// one lane group per long run: pieces are combined in order, then one SGD update
-template <typename V, int LPR> __global__ __launch_bounds__(256) void bwd_long_final_kernel(BwdArgs a)
-{
-    constexpr int GPB = 256 / LPR;
-    constexpr int VW = sizeof(V) / sizeof(float);
-    int n_long = a.counters[0];
-    if (n_long > a.long_cap)
-        n_long = a.long_cap;
-    const int g = threadIdx.x / LPR, l = threadIdx.x % LPR;
     const int ncols = a.dim / VW;
-    for (int q = blockIdx.x * GPB + g; q < n_long; q += gridDim.x * GPB) {
-        const LongRun r = a.longq[q];
-        if (r.piece_base + r.n_pieces > a.piece_cap)
-            continue; // cannot happen with the documented workspace size
-        for (int c = l; c < ncols; c += LPR) {
-            V acc = bwd_vec<V>::zero();
-            for (int i = 0; i < r.n_pieces; ++i)
-                bwd_vec<V>::add(acc, ((const V *)(a.partial + (int64_t)(r.piece_base + i) * a.dim))[c]);
-            V *wp = (V *)a.W[r.z] + (int64_t)r.key * ncols + c;
+    const int first_sid = sid - sp.local;
+    for (int c0 = 0; c0 < ncols; c0 += LPR) {
+        const int c = c0 + l;
+        V acc = bwd_vec<V>::zero();
+        if (c < ncols) {
+            for (int j = g; j < n_follow; j += G)
+                bwd_vec<V>::add(acc, ((const V *)(a.partial + (int64_t)(first_sid + sp.local + 1 + j) * 2 * a.dim))[c]);
+        }
+#pragma unroll
+        for (int m = LPR; m < FAE_WAVE; m <<= 1) {
+            const V o = bwd_shfl<V>(acc, lane ^ m);
+            bwd_vec<V>::add(acc, o);
+        }
+        if (g == 0 && c < ncols) {
+            bwd_vec<V>::add(acc, ((const V *)(a.partial + ((int64_t)sid * 2 + 1) * a.dim))[c]);
+            V *wp = (V *)a.W[sp.z] + (int64_t)k * ncols + c;
             *wp = bwd_vec<V>::sgd(*wp, acc, a.lr);
         }
     }
@@ -474,7 +679,7 @@ namespace {
 struct BwdPlan {
     int64_t N;
     int64_t tiles;
-    int64_t long_cap, piece_cap;
+    int64_t max_spans; // with the smallest span
     int64_t dbg_tiles;
 };
 
@@ -483,28 +688,35 @@ BwdPlan bwd_plan(int nt, const int64_t *h_n_lookups)
     BwdPlan p;
     p.N = 0;
     p.tiles = 0;
+    p.max_spans = 0;
     for (int z = 0; z < nt; ++z) {
         p.N += h_n_lookups[z];
         p.tiles += (h_n_lookups[z] + SORT_TILE - 1) / SORT_TILE;
+        p.max_spans += (h_n_lookups[z] + BWD_SPAN_MIN - 1) / BWD_SPAN_MIN;
     }
-    p.long_cap = p.N / (BWD_LONG + 1) + 1;
-    p.piece_cap = p.N / BWD_PIECE + p.long_cap + 1;
     p.dbg_tiles = (p.N + DBG_TILE - 1) / DBG_TILE;
     return p;
 }
 
+// lookups per wave: long spans amortise the border handling, short ones fill the chip
+int bwd_span(const BwdPlan &p, int n_cu)
+{
+    int span = BWD_SPAN_MAX;
+    while (span > BWD_SPAN_MIN && p.N / span < 16LL * n_cu)
+        span >>= 1;
+    return span;
+}
+
 struct BwdWs {
     int32_t *keys[2], *vals[2];
-    int32_t *hist, *tot, *counters;
-    LongRun *longq;
-    Piece *pieces;
+    int32_t *hist, *tot;
     float *partial;
     int32_t *dbg_tile_sums, *dbg_rstart;
     bool ok;
     size_t used;
 };
 
-BwdWs bwd_carve(void *ws, size_t bytes, const BwdPlan &p, int nt, int dim)
+BwdWs bwd_carve(void *ws, size_t bytes, const BwdPlan &p, int nt, int dim, int span)
 {
     fae_carver cv(ws, bytes);
     BwdWs w;
@@ -514,10 +726,7 @@ BwdWs bwd_carve(void *ws, size_t bytes, const BwdPlan &p, int nt, int dim)
     }
     w.hist = cv.take<int32_t>((size_t)RADIX * p.tiles + 1);
     w.tot = cv.take<int32_t>((size_t)nt * RADIX);
-    w.counters = cv.take<int32_t>(64);
-    w.longq = cv.take<LongRun>((size_t)p.long_cap);
-    w.pieces = cv.take<Piece>((size_t)p.piece_cap);
-    w.partial = cv.take<float>((size_t)p.piece_cap * dim);
+    w.partial = cv.take<float>((size_t)(p.max_spans * BWD_SPAN_MIN / span + nt + 1) * 2 * dim);
     w.dbg_tile_sums = cv.take<int32_t>((size_t)p.dbg_tiles + 2);
     w.dbg_rstart = cv.take<int32_t>((size_t)p.N + 2);
     w.ok = cv.ok;
@@ -525,18 +734,14 @@ BwdWs bwd_carve(void *ws, size_t bytes, const BwdPlan &p, int nt, int dim)
     return w;
 }
 
-template <typename V, int LPR> void launch_reduce(fae_ctx *ctx, const BwdArgs &a, int blocks)
-{
-    hipLaunchKernelGGL((bwd_reduce_kernel<V, LPR>), dim3(blocks), dim3(256), 0, ctx->stream, a);
-}
-template <typename V, int LPR> void launch_long(fae_ctx *ctx, const BwdArgs &a, int piece_blocks, int final_blocks)
+template <typename V, int LPR> void launch_reduce(fae_ctx *ctx, const BwdArgs &a)
 {
     {
-        fae_ktimer kt(ctx, FAE_K_LONG_PIECE);
-        hipLaunchKernelGGL((bwd_long_piece_kernel<V, LPR>), dim3(piece_blocks), dim3(256), 0, ctx->stream, a);
+        fae_ktimer kt(ctx, FAE_K_BWD_REDUCE);
+        hipLaunchKernelGGL((bwd_reduce_kernel<V, LPR>), dim3((a.n_spans + 3) / 4), dim3(256), 0, ctx->stream, a);
     }
-    fae_ktimer kt(ctx, FAE_K_LONG_FINAL);
-    hipLaunchKernelGGL((bwd_long_final_kernel<V, LPR>), dim3(final_blocks), dim3(256), 0, ctx->stream, a);
+    fae_ktimer kt(ctx, FAE_K_BWD_FIXUP);
+    hipLaunchKernelGGL((bwd_fixup_kernel<V, LPR>), dim3((a.n_spans + 3) / 4), dim3(256), 0, ctx->stream, a);
 }
 
 #define BWD_LPR_SWITCH(V, lpr, CALL)      \
@@ -557,7 +762,8 @@ extern "C" size_t fae_bwd_workspace_bytes(const fae_tables *hot_tables, int64_t 
     if (!hot_tables || !h_n_lookups || hot_tables->n_tables < 1 || hot_tables->n_tables > FAE_MAX_TABLES)
         return 0;
     BwdPlan p = bwd_plan(hot_tables->n_tables, h_n_lookups);
-    BwdWs w = bwd_carve((void *)256, (size_t)-1, p, hot_tables->n_tables, hot_tables->dim);
+    // sized for the smallest span, so the size does not depend on the device's CU count
+    BwdWs w = bwd_carve((void *)256, (size_t)-1, p, hot_tables->n_tables, hot_tables->dim, BWD_SPAN_MIN);
     return w.used + 256;
 }
 
@@ -593,14 +799,14 @@ extern "C" int32_t fae_embbag_bwd_sgd(fae_ctx *ctx, const fae_tables *hot_tables
         return fae_fail(ctx, FAE_EINVAL, "fae_embbag_bwd_sgd: incomplete debug outputs");
     if (!ws)
         return fae_fail(ctx, FAE_ENOSPC, "fae_embbag_bwd_sgd: null workspace");
-    BwdWs w = bwd_carve(ws, ws_bytes, plan, nt, dim);
+    const int span = bwd_span(plan, ctx->n_cu);
+    BwdWs w = bwd_carve(ws, ws_bytes, plan, nt, dim, BWD_SPAN_MIN);
     if (!w.ok)
         return fae_fail(ctx, FAE_ENOSPC, "fae_embbag_bwd_sgd: workspace too small (%zu needed)", w.used);
 
     BwdArgs a;
     memset(&a, 0, sizeof(a));
     bool vec = (dim % 4 == 0) && (gout_row_stride % 4 == 0) && (((uintptr_t)gout) % 16 == 0);
-    int64_t max_hot = 0;
     int64_t lookups = 0, tiles = 0;
     for (int z = 0; z < nt; ++z) {
         if (!h_hotW[z] && hot_tables->h_rows[z] > 0)
@@ -611,14 +817,30 @@ extern "C" int32_t fae_embbag_bwd_sgd(fae_ctx *ctx, const fae_tables *hot_tables
         a.n_hot[z] = (int32_t)hot_tables->h_rows[z];
         if (((uintptr_t)h_hotW[z]) % 16 != 0)
             vec = false;
-        if (hot_tables->h_rows[z] > max_hot)
-            max_hot = hot_tables->h_rows[z];
         a.seg_start[z] = (int32_t)lookups;
         a.tile_start[z] = (int32_t)tiles;
         lookups += hot_batch->h_n_lookups[z];
         tiles += (hot_batch->h_n_lookups[z] + SORT_TILE - 1) / SORT_TILE;
     }
     a.seg_start[nt] = (int32_t)lookups;
+    a.tile_start[nt] = (int32_t)tiles;
+    // Tables whose lookups fit one workgroup are sorted in LDS; they take no part in the
+    // global passes (zero tiles, zero key blocks).
+    bool in_lds[FAE_MAX_TABLES];
+    int n_lds = 0;
+    int64_t max_hot_global = 0;
+    tiles = 0;
+    for (int z = 0; z < nt; ++z) {
+        const int64_t nl = hot_batch->h_n_lookups[z];
+        in_lds[z] = ctx->opt_sort != 1 && nl > 0 && nl <= LSORT_MAX;
+        if (in_lds[z])
+            ++n_lds;
+        else if (nl > 0 && hot_tables->h_rows[z] > max_hot_global)
+            max_hot_global = hot_tables->h_rows[z];
+        a.tile_start[z] = (int32_t)tiles;
+        if (!in_lds[z])
+            tiles += (nl + SORT_TILE - 1) / SORT_TILE;
+    }
     a.tile_start[nt] = (int32_t)tiles;
     a.n_tables = nt;
     a.dim = dim;
@@ -628,37 +850,33 @@ extern "C" int32_t fae_embbag_bwd_sgd(fae_ctx *ctx, const fae_tables *hot_tables
     a.gout = gout;
     a.gout_stride = gout_row_stride;
     a.lr = lr;
-    a.longq = w.longq;
-    a.pieces = w.pieces;
     a.partial = w.partial;
-    a.counters = w.counters;
-    a.long_cap = (int32_t)plan.long_cap;
-    a.piece_cap = (int32_t)plan.piece_cap;
+    a.span = span;
     a.status = ctx->d_block;
 
-    // 1. keys (also clears the long-run counters for this call)
-    rc = fae_fill_u32(ctx, w.counters, 64, 0u);
-    if (rc != FAE_OK)
-        return rc;
+    // 1. keys
     {
         int64_t blocks = 0;
         for (int z = 0; z < nt; ++z) {
             a.blk_start[z] = (int32_t)blocks;
-            blocks += (hot_batch->h_n_lookups[z] + 255) / 256;
+            if (!in_lds[z])
+                blocks += (hot_batch->h_n_lookups[z] + 255) / 256;
         }
         a.blk_start[nt] = (int32_t)blocks;
         a.keys_in = w.keys[0];
         a.vals_in = w.vals[0];
-        fae_ktimer kt(ctx, FAE_K_BWD_KEYS);
-        hipLaunchKernelGGL(bwd_keys_kernel, dim3((unsigned)blocks), dim3(256), 0, ctx->stream, a);
-        FAE_LAUNCH_CHECK(ctx);
+        if (blocks > 0) {
+            fae_ktimer kt(ctx, FAE_K_BWD_KEYS);
+            hipLaunchKernelGGL(bwd_keys_kernel, dim3((unsigned)blocks), dim3(256), 0, ctx->stream, a);
+            FAE_LAUNCH_CHECK(ctx);
+        }
     }
     // 2. sort: only the bits a slot (or the invalid marker n_hot) can occupy
     int bits = 1;
-    while ((max_hot >> bits) != 0)
+    while ((max_hot_global >> bits) != 0)
         ++bits;
-    const int passes = (bits + RADIX_BITS - 1) / RADIX_BITS;
-    const int digit_bits = (bits + passes - 1) / passes;
+    const int passes = tiles > 0 ? (bits + RADIX_BITS - 1) / RADIX_BITS : 0;
+    const int digit_bits = passes > 0 ? (bits + passes - 1) / passes : RADIX_BITS;
     int cur = 0;
     for (int pass = 0; pass < passes; ++pass) {
         a.shift = pass * digit_bits;
@@ -688,53 +906,69 @@ extern "C" int32_t fae_embbag_bwd_sgd(fae_ctx *ctx, const fae_tables *hot_tables
     a.vals_in = w.vals[cur];
     a.keys_out = nullptr;
     a.vals_out = nullptr;
+    if (n_lds > 0) { // small tables: straight from the slots into the final buffer
+        LsortArgs la;
+        memset(&la, 0, sizeof(la));
+        // parts per table: enough workgroups to occupy the chip, never lists below ~512 lookups
+        int want = 1;
+        while (want < 16 && n_lds * want * 2 <= ctx->n_cu)
+            want <<= 1;
+        int nb = 0;
+        for (int z = 0; z < nt; ++z) {
+            la.slots[z] = a.slots[z];
+            la.offsets[z] = a.offsets[z];
+            la.n_hot[z] = a.n_hot[z];
+            la.seg_start[z] = a.seg_start[z];
+            la.blk_start[z] = nb;
+            if (!in_lds[z])
+                continue;
+            int kbits = 1; // bits of the largest key (n_hot itself marks an invalid slot)
+            while ((hot_tables->h_rows[z] >> kbits) != 0)
+                ++kbits;
+            int parts = want;
+            while (parts > 1 && hot_batch->h_n_lookups[z] / parts < 512)
+                parts >>= 1;
+            int pbits = 0;
+            while ((1 << pbits) < parts)
+                ++pbits;
+            if (pbits > kbits)
+                pbits = kbits;
+            la.part_shift[z] = kbits - pbits;
+            // parts that can hold a key: 0 .. (n_hot >> shift)
+            nb += (int)(hot_tables->h_rows[z] >> la.part_shift[z]) + 1;
+        }
+        la.blk_start[nt] = nb;
+        la.seg_start[nt] = a.seg_start[nt];
+        la.n_tables = nt;
+        la.n_samples = a.n_samples;
+        la.keys_out = w.keys[cur];
+        la.vals_out = w.vals[cur];
+        la.status = ctx->d_block;
+        fae_ktimer kt(ctx, FAE_K_LDS_SORT);
+        hipLaunchKernelGGL(lds_sort_kernel, dim3(nb), dim3(LSORT_THREADS), 0, ctx->stream, la);
+        FAE_LAUNCH_CHECK(ctx);
+    }
 
-    // 3. reduce + SGD
+    // 3 + 4. reduce + SGD, then the runs that cross span borders
     const int ncols = vec ? dim / 4 : dim;
     int lpr = 1;
     while (lpr < ncols && lpr < 64)
         lpr <<= 1;
     {
-        const int gpb = 256 / lpr;
-        int64_t blocks = 0;
+        int64_t spans = 0;
         for (int z = 0; z < nt; ++z) {
-            a.blk_start[z] = (int32_t)blocks;
-            int64_t chunks = (hot_batch->h_n_lookups[z] + BWD_CHUNK - 1) / BWD_CHUNK;
-            blocks += (chunks + gpb - 1) / gpb;
+            a.blk_start[z] = (int32_t)spans;
+            spans += (hot_batch->h_n_lookups[z] + span - 1) / span;
         }
-        a.blk_start[nt] = (int32_t)blocks;
-        const int nb = (int)blocks;
-        fae_ktimer kt(ctx, FAE_K_BWD_REDUCE);
-#define CALL_REDUCE(V, L) launch_reduce<V, L>(ctx, a, nb)
+        a.blk_start[nt] = (int32_t)spans;
+        a.n_spans = (int32_t)spans;
+#define CALL_REDUCE(V, L) launch_reduce<V, L>(ctx, a)
         if (vec) {
             BWD_LPR_SWITCH(float4, lpr, CALL_REDUCE)
         } else {
             BWD_LPR_SWITCH(float, lpr, CALL_REDUCE)
         }
 #undef CALL_REDUCE
-        FAE_LAUNCH_CHECK(ctx);
-    }
-    // 4. long runs
-    {
-        int prep_blocks = (int)((plan.long_cap + 255) / 256);
-        if (prep_blocks > 256)
-            prep_blocks = 256;
-        {
-            fae_ktimer kt(ctx, FAE_K_LONG_PREP);
-            hipLaunchKernelGGL(bwd_long_prep_kernel, dim3(prep_blocks), dim3(256), 0, ctx->stream, a);
-            FAE_LAUNCH_CHECK(ctx);
-        }
-        int piece_blocks = (int)(plan.piece_cap < 4 * ctx->n_cu ? plan.piece_cap : 4 * ctx->n_cu);
-        int final_blocks = (int)((plan.long_cap + (256 / lpr) - 1) / (256 / lpr));
-        if (final_blocks > 2 * ctx->n_cu)
-            final_blocks = 2 * ctx->n_cu;
-#define CALL_LONG(V, L) launch_long<V, L>(ctx, a, piece_blocks, final_blocks)
-        if (vec) {
-            BWD_LPR_SWITCH(float4, lpr, CALL_LONG)
-        } else {
-            BWD_LPR_SWITCH(float, lpr, CALL_LONG)
-        }
-#undef CALL_LONG
         FAE_LAUNCH_CHECK(ctx);
     }
     // optional: distinct slots and multiplicities

@@ -173,9 +173,9 @@ extern "C" int32_t fae_timing_read(fae_ctx *ctx, int32_t kernel_class, double *h
 
 extern "C" const char *fae_kernel_name(int32_t k)
 {
-    static const char *names[FAE_K_COUNT] = {"fwd",        "bwd_keys",   "sort_hist",  "sort_colscan", "sort_scatter",
-                                             "bwd_reduce", "long_prep",  "long_piece", "long_final",   "lds_sort",
-                                             "fill",       "profile",    "partition",  "build",        "other"};
+    static const char *names[FAE_K_COUNT] = {"fwd",        "bwd_keys",  "sort_hist", "sort_colscan", "sort_scatter",
+                                             "bwd_reduce", "bwd_fixup", "lds_sort",  "fill",         "profile",
+                                             "partition",  "build",     "other"};
     return (k >= 0 && k < FAE_K_COUNT) ? names[k] : "?";
 }
 
@@ -193,6 +193,8 @@ extern "C" int32_t fae_set_option(fae_ctx *ctx, const char *name, int64_t value)
         ctx->opt_fwd = value;
     else if (!strcmp(name, "sort_variant") && value >= 0 && value <= 2)
         ctx->opt_sort = value;
+    else if (!strcmp(name, "fwd_stream_out") && value >= 0 && value <= 1)
+        ctx->opt_fwd_stream = value;
     else
         return fae_fail(ctx, FAE_EINVAL, "fae_set_option: unknown option or value: %s=%lld", name,
                         (long long)value);

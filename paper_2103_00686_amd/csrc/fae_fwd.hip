@@ -23,6 +23,7 @@ struct FwdArgs {
     int64_t out_stride;
     float *out;
     uint32_t *status;
+    int32_t stream_out; // non-temporal stores for the pooled output
 };
 
 template <typename V> struct vec_ops;
@@ -101,6 +102,70 @@ template <typename V, int LPR> __global__ __launch_bounds__(256) void fwd_group_
     }
 }
 
+typedef float fae_v4f __attribute__((ext_vector_type(4)));
+// streaming store: the pooled output is written once and not read again by this kernel
+__device__ __forceinline__ void fwd_store(float4 *p, const float4 &v, bool stream)
+{
+    if (stream)
+        __builtin_nontemporal_store(*(const fae_v4f *)&v, (fae_v4f *)p);
+    else
+        *p = v;
+}
+__device__ __forceinline__ void fwd_store(float *p, const float &v, bool stream)
+{
+    if (stream)
+        __builtin_nontemporal_store(v, p);
+    else
+        *p = v;
+}
+
+// One-hot tables (one lookup per sample): a wave takes 64 consecutive samples, reads their
+// 64 slots with one coalesced load and then copies rows, 64/LPR rows per step, with the
+// loads of up to 16 steps in flight before the first store.
+template <typename V, int LPR> __global__ __launch_bounds__(256) void fwd_onehot_kernel(FwdArgs a)
+{
+    constexpr int G = FAE_WAVE / LPR;
+    constexpr int STEPS = FAE_WAVE / G;
+    constexpr int UN = STEPS < 16 ? STEPS : 16;
+    const int z = fae_find_table(a.blk_start, a.n_tables, blockIdx.x);
+    const int bl = blockIdx.x - a.blk_start[z];
+    const int lane = fae_lane(), g = lane / LPR, l = lane % LPR;
+    const int64_t s0 = ((int64_t)bl * (256 / FAE_WAVE) + threadIdx.x / FAE_WAVE) * FAE_WAVE;
+    if (s0 >= a.n_samples)
+        return;
+    const int n_hot = a.n_hot[z];
+    int sreg = -1;
+    if (s0 + lane < a.n_samples) {
+        sreg = a.slots[z][s0 + lane];
+        if ((unsigned)sreg >= (unsigned)n_hot) {
+            fae_flag(a.status, FAE_STATUS_ERANGE);
+            sreg = -1; // pooled row of an invalid slot: zeros
+        }
+    }
+    const int ncols = a.dim / (int)(sizeof(V) / sizeof(float));
+    const V *W = (const V *)a.W[z];
+    float *obase = a.out + (int64_t)z * a.dim;
+    for (int c0 = 0; c0 < ncols; c0 += LPR) {
+        const int c = c0 + l;
+        const bool active = c < ncols;
+#pragma unroll
+        for (int i0 = 0; i0 < STEPS; i0 += UN) {
+            V v[UN];
+#pragma unroll
+            for (int u = 0; u < UN; ++u) {
+                const int sl = __shfl(sreg, (i0 + u) * G + g, FAE_WAVE);
+                v[u] = (active && sl >= 0) ? W[(int64_t)sl * ncols + c] : vec_ops<V>::zero();
+            }
+#pragma unroll
+            for (int u = 0; u < UN; ++u) {
+                const int64_t s = s0 + (i0 + u) * G + g;
+                if (active && s < a.n_samples)
+                    fwd_store((V *)(obase + s * a.out_stride) + c, v[u], a.stream_out != 0);
+            }
+        }
+    }
+}
+
 template <typename V, int LPR> __global__ __launch_bounds__(256) void fwd_wave_kernel(FwdArgs a)
 {
     constexpr int G = FAE_WAVE / LPR; // lane groups per wave
@@ -154,24 +219,26 @@ template <typename V, int LPR> __global__ __launch_bounds__(256) void fwd_wave_k
     }
 }
 
-template <typename V, int LPR> static void fwd_launch(fae_ctx *ctx, const FwdArgs &a, bool wave, int total_blocks)
+template <typename V, int LPR> static void fwd_launch(fae_ctx *ctx, const FwdArgs &a, int kind, int total_blocks)
 {
-    if (wave)
+    if (kind == 2)
+        hipLaunchKernelGGL((fwd_onehot_kernel<V, LPR>), dim3(total_blocks), dim3(256), 0, ctx->stream, a);
+    else if (kind == 1)
         hipLaunchKernelGGL((fwd_wave_kernel<V, LPR>), dim3(total_blocks), dim3(256), 0, ctx->stream, a);
     else
         hipLaunchKernelGGL((fwd_group_kernel<V, LPR>), dim3(total_blocks), dim3(256), 0, ctx->stream, a);
 }
 
-template <typename V> static void fwd_dispatch(fae_ctx *ctx, const FwdArgs &a, int lpr, bool wave, int total_blocks)
+template <typename V> static void fwd_dispatch(fae_ctx *ctx, const FwdArgs &a, int lpr, int kind, int total_blocks)
 {
     switch (lpr) {
-    case 1: fwd_launch<V, 1>(ctx, a, wave, total_blocks); break;
-    case 2: fwd_launch<V, 2>(ctx, a, wave, total_blocks); break;
-    case 4: fwd_launch<V, 4>(ctx, a, wave, total_blocks); break;
-    case 8: fwd_launch<V, 8>(ctx, a, wave, total_blocks); break;
-    case 16: fwd_launch<V, 16>(ctx, a, wave, total_blocks); break;
-    case 32: fwd_launch<V, 32>(ctx, a, wave, total_blocks); break;
-    default: fwd_launch<V, 64>(ctx, a, wave, total_blocks); break;
+    case 1: fwd_launch<V, 1>(ctx, a, kind, total_blocks); break;
+    case 2: fwd_launch<V, 2>(ctx, a, kind, total_blocks); break;
+    case 4: fwd_launch<V, 4>(ctx, a, kind, total_blocks); break;
+    case 8: fwd_launch<V, 8>(ctx, a, kind, total_blocks); break;
+    case 16: fwd_launch<V, 16>(ctx, a, kind, total_blocks); break;
+    case 32: fwd_launch<V, 32>(ctx, a, kind, total_blocks); break;
+    default: fwd_launch<V, 64>(ctx, a, kind, total_blocks); break;
     }
 }
 
@@ -195,8 +262,6 @@ extern "C" int32_t fae_embbag_fwd(fae_ctx *ctx, const fae_tables *hot_tables, co
     FwdArgs a;
     memset(&a, 0, sizeof(a));
     bool vec = (dim % 4 == 0) && (out_row_stride % 4 == 0) && (((uintptr_t)out) % 16 == 0);
-    int64_t total_lookups = 0;
-    bool any_csr = false;
     for (int z = 0; z < nt; ++z) {
         if (!h_hotW[z] && hot_tables->h_rows[z] > 0)
             return fae_fail(ctx, FAE_EINVAL, "fae_embbag_fwd: null weights for table %d", z);
@@ -207,40 +272,75 @@ extern "C" int32_t fae_embbag_fwd(fae_ctx *ctx, const fae_tables *hot_tables, co
         a.n_lookups[z] = (int32_t)hot_batch->h_n_lookups[z];
         if (((uintptr_t)h_hotW[z]) % 16 != 0)
             vec = false;
-        total_lookups += hot_batch->h_n_lookups[z];
-        if (a.offsets[z])
-            any_csr = true;
     }
     const int ncols = vec ? dim / 4 : dim;
     int lpr = 1;
     while (lpr < ncols && lpr < 64)
         lpr <<= 1;
-    // wave-per-bag pays once a bag keeps every lane group of the wave busy for a few rounds
     const int groups = 64 / lpr;
-    double avg_len = (double)total_lookups / ((double)S * nt);
-    bool wave = any_csr && groups > 1 && avg_len >= 2.0 * groups;
-    if (ctx->opt_fwd == 1)
-        wave = false;
-    if (ctx->opt_fwd == 2)
-        wave = groups > 1;
-    const int bags_per_block = wave ? 4 : 256 / lpr;
-    const int64_t blk_per_table = (S + bags_per_block - 1) / bags_per_block;
-    if (blk_per_table * nt >= 2147483647LL)
-        return fae_fail(ctx, FAE_EINVAL, "fae_embbag_fwd: batch too large for one launch");
-    for (int z = 0; z <= nt; ++z)
-        a.blk_start[z] = (int32_t)(blk_per_table * z);
     a.n_tables = nt;
     a.dim = dim;
     a.n_samples = (int32_t)S;
     a.out_stride = out_row_stride;
     a.out = out;
     a.status = ctx->d_block;
-    const int total_blocks = (int)(blk_per_table * nt);
-    fae_ktimer kt(ctx, FAE_K_FWD);
-    if (vec)
-        fwd_dispatch<float4>(ctx, a, lpr, wave, total_blocks);
-    else
-        fwd_dispatch<float>(ctx, a, lpr, wave, total_blocks);
-    FAE_LAUNCH_CHECK(ctx);
+    a.stream_out = ctx->opt_fwd_stream != 0;
+    // one-hot tables: 256 samples per workgroup
+    if (ctx->opt_fwd == 0) {
+        const int64_t per_table = (S + 255) / 256;
+        int64_t blocks = 0;
+        for (int z = 0; z < nt; ++z) {
+            a.blk_start[z] = (int32_t)blocks;
+            if (!a.offsets[z])
+                blocks += per_table;
+        }
+        a.blk_start[nt] = (int32_t)blocks;
+        if (blocks >= 2147483647LL)
+            return fae_fail(ctx, FAE_EINVAL, "fae_embbag_fwd: batch too large for one launch");
+        if (blocks > 0) {
+            fae_ktimer kt(ctx, FAE_K_FWD);
+            if (vec)
+                fwd_dispatch<float4>(ctx, a, lpr, 2, (int)blocks);
+            else
+                fwd_dispatch<float>(ctx, a, lpr, 2, (int)blocks);
+            FAE_LAUNCH_CHECK(ctx);
+        }
+    }
+    // tables with offsets (and every table when a lane mapping is forced)
+    {
+        int64_t csr_lookups = 0;
+        int n_csr = 0;
+        for (int z = 0; z < nt; ++z)
+            if (a.offsets[z] || ctx->opt_fwd != 0) {
+                csr_lookups += hot_batch->h_n_lookups[z];
+                ++n_csr;
+            }
+        if (n_csr > 0) {
+            // wave-per-bag pays once a bag keeps every lane group of the wave busy for a few rounds
+            const double avg_len = (double)csr_lookups / ((double)S * n_csr);
+            bool wave = groups > 1 && avg_len >= 2.0 * groups;
+            if (ctx->opt_fwd == 1)
+                wave = false;
+            if (ctx->opt_fwd == 2)
+                wave = groups > 1;
+            const int bags_per_block = wave ? 4 : 256 / lpr;
+            const int64_t per_table = (S + bags_per_block - 1) / bags_per_block;
+            int64_t blocks = 0;
+            for (int z = 0; z < nt; ++z) {
+                a.blk_start[z] = (int32_t)blocks;
+                if (a.offsets[z] || ctx->opt_fwd != 0)
+                    blocks += per_table;
+            }
+            a.blk_start[nt] = (int32_t)blocks;
+            if (blocks >= 2147483647LL)
+                return fae_fail(ctx, FAE_EINVAL, "fae_embbag_fwd: batch too large for one launch");
+            fae_ktimer kt(ctx, FAE_K_FWD);
+            if (vec)
+                fwd_dispatch<float4>(ctx, a, lpr, wave ? 1 : 0, (int)blocks);
+            else
+                fwd_dispatch<float>(ctx, a, lpr, wave ? 1 : 0, (int)blocks);
+            FAE_LAUNCH_CHECK(ctx);
+        }
+    }
     return FAE_OK;
 }

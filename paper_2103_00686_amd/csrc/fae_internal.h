@@ -35,6 +35,7 @@ struct fae_ctx {
     int64_t opt_profile = 0; // 0 auto, 1 global atomics, 2 LDS-privatised
     int64_t opt_fwd = 0;     // 0 auto, 1 group-per-bag, 2 wave-per-bag
     int64_t opt_sort = 0;    // 0 auto, 1 global radix, 2 LDS per table
+    int64_t opt_fwd_stream = 1; // non-temporal stores for the pooled output
     char err[512] = {0};
     // per-kernel timing
     bool timing = false;
