@@ -131,14 +131,16 @@ int32_t fae_profile(fae_ctx *ctx, const fae_tables *tables, const fae_batch *chu
 
 /* ---- a2: hot cutoff (Eq. 1, Eq. 2; budget L of Sec. 4.1) ------------------- */
 /* Budget mode.  Tables with rows_z*dim*4 < small_table_bytes are wholly hot
- * (cutoff 0).  Every other table uses H_z(c) = ceil(c * h_T[z] / n_profile_samples)
- * and a row is hot iff count >= H_z.  Finds the smallest integer c >= 0 whose hot
+ * (cutoff 0).  Every other table uses H_z(c) = ceil(c * h_T[z] / t_denom) and a row
+ * is hot iff count >= H_z: the paper's threshold t, a fraction of a table's accesses,
+ * on the integer grid t = c / t_denom.  Finds the smallest integer c >= 0 whose hot
  * rows (small tables included) fit budget_bytes.  h_T[z] is the number of profiled
- * lookups into table z.  Outputs (host): *h_c_out, h_cutoff_out[z], h_n_hot_out[z].
+ * lookups into table z; t_denom = max_z h_T[z] makes one step of c one access for the
+ * most-accessed table (for one-hot tables that is the number of profiled samples).  Outputs (host): *h_c_out, h_cutoff_out[z], h_n_hot_out[z].
  * Synchronises.  FAE_ENOSPC if the small tables alone exceed the budget. */
 size_t fae_choose_cutoff_workspace_bytes(const fae_tables *tables);
 int32_t fae_choose_cutoff(fae_ctx *ctx, const fae_tables *tables, const uint32_t *const *h_counts,
-                          const int64_t *h_T, int64_t n_profile_samples, int64_t budget_bytes,
+                          const int64_t *h_T, int64_t t_denom, int64_t budget_bytes,
                           int64_t small_table_bytes, int64_t *h_c_out, uint32_t *h_cutoff_out,
                           int64_t *h_n_hot_out, void *ws, size_t ws_bytes);
 /* Explicit mode helper: number of rows with count >= h_cutoff[z].  Synchronises. */

@@ -82,15 +82,17 @@ static uint32_t scaled_cutoff(int64_t c, int64_t T, int64_t n)
 /* Budget mode (Sec. 4.1: "the top h entries that fit L", expressed through one
  * count threshold as the paper's t is).  Tables smaller than small_table_bytes
  * are wholly hot (Sec. 4.1.2, Embedding Logger); every other table z uses the
- * cutoff H_z(c) = ceil(c * T_z / n_profile_samples); the answer is the smallest
- * c >= 0 whose hot rows (small tables included) fit budget_bytes. */
+ * cutoff H_z(c) = ceil(c * T_z / t_denom), i.e. the threshold t = c / t_denom as a
+ * fraction of the table's accesses T_z (Sec. 4.1: hot entries have >= t * T accesses);
+ * the answer is the smallest c >= 0 whose hot rows (small tables included) fit
+ * budget_bytes.  The caller fixes the grid of t through t_denom. */
 int orc_budget_cutoff(int32_t n_tables, int32_t dim, const int64_t *rows,
                       const uint32_t *const *cnt, const int64_t *T,
-                      int64_t n_profile_samples, int64_t budget_bytes,
+                      int64_t t_denom, int64_t budget_bytes,
                       int64_t small_table_bytes, int64_t *c_out,
                       uint32_t *H_out, int64_t *n_hot_out)
 {
-    if (n_tables <= 0 || dim <= 0 || n_profile_samples <= 0)
+    if (n_tables <= 0 || dim <= 0 || t_denom <= 0)
         return ORC_EINVAL;
     int64_t row_bytes = (int64_t)dim * 4;
     uint32_t max_cnt = 0;
@@ -106,7 +108,7 @@ int orc_budget_cutoff(int32_t n_tables, int32_t dim, const int64_t *rows,
             if (rows[z] * row_bytes < small_table_bytes)
                 H = 0u;
             else
-                H = scaled_cutoff(c, T[z], n_profile_samples);
+                H = scaled_cutoff(c, T[z], t_denom);
             if (H != 0u && H <= max_cnt)
                 all_above = 0;
             H_out[z] = H;

@@ -98,7 +98,7 @@ def count_hot(cnt: np.ndarray, H: int) -> int:
     return int(lib().orc_count_hot(_p(cnt), C.c_int64(cnt.size), C.c_uint32(H)))
 
 
-def budget_cutoff(dim: int, cnts: List[np.ndarray], T: Sequence[int], n_profile_samples: int,
+def budget_cutoff(dim: int, cnts: List[np.ndarray], T: Sequence[int], t_denom: int,
                   budget_bytes: int, small_table_bytes: int = 1 << 20):
     """Returns (c, H[z], n_hot[z])."""
     nt = len(cnts)
@@ -109,7 +109,7 @@ def budget_cutoff(dim: int, cnts: List[np.ndarray], T: Sequence[int], n_profile_
     H = np.zeros(nt, dtype=np.uint32)
     nh = np.zeros(nt, dtype=np.int64)
     rc = lib().orc_budget_cutoff(C.c_int32(nt), C.c_int32(dim), _p(rows), _ptr_array(cnts), _p(Tn),
-                                 C.c_int64(n_profile_samples), C.c_int64(budget_bytes),
+                                 C.c_int64(t_denom), C.c_int64(budget_bytes),
                                  C.c_int64(small_table_bytes), C.byref(c_out), _p(H), _p(nh))
     _check(rc, "budget_cutoff")
     return int(c_out.value), H, nh

@@ -215,7 +215,7 @@ def fae_choose_cutoff_workspace_bytes(tables: Tables) -> int:
 
 
 def fae_choose_cutoff(ctx: Context, tables: Tables, counts: List[torch.Tensor], T: Sequence[int],
-                      n_profile_samples: int, budget_bytes: int, small_table_bytes: int, ws: torch.Tensor):
+                      t_denom: int, budget_bytes: int, small_table_bytes: int, ws: torch.Tensor):
     """Returns (c, cutoff[z], n_hot[z]) as Python ints."""
     nt = len(tables.rows)
     t = tables.c()
@@ -224,7 +224,7 @@ def fae_choose_cutoff(ctx: Context, tables: Tables, counts: List[torch.Tensor], 
     cut = (C.c_uint32 * nt)()
     nh = (C.c_int64 * nt)()
     ctx.check(load().fae_choose_cutoff(ctx._h, C.byref(t), _ptrs(counts, torch.int32), Ta,
-                                       C.c_int64(n_profile_samples), C.c_int64(budget_bytes),
+                                       C.c_int64(t_denom), C.c_int64(budget_bytes),
                                        C.c_int64(small_table_bytes), C.byref(c_out), cut, nh,
                                        _ptr(ws, torch.uint8), C.c_size_t(ws.numel())))
     return int(c_out.value), list(cut), list(nh)

@@ -324,14 +324,14 @@ extern "C" int32_t fae_count_hot(fae_ctx *ctx, const fae_tables *tables, const u
 }
 
 extern "C" int32_t fae_choose_cutoff(fae_ctx *ctx, const fae_tables *tables, const uint32_t *const *h_counts,
-                                     const int64_t *h_T, int64_t n_profile_samples, int64_t budget_bytes,
+                                     const int64_t *h_T, int64_t t_denom, int64_t budget_bytes,
                                      int64_t small_table_bytes, int64_t *h_c_out, uint32_t *h_cutoff_out,
                                      int64_t *h_n_hot_out, void *ws, size_t ws_bytes)
 {
     int32_t rc = fae_check_tables(ctx, tables, "fae_choose_cutoff");
     if (rc != FAE_OK)
         return rc;
-    if (!h_counts || !h_T || !h_c_out || !h_cutoff_out || !h_n_hot_out || n_profile_samples <= 0 || budget_bytes < 0)
+    if (!h_counts || !h_T || !h_c_out || !h_cutoff_out || !h_n_hot_out || t_denom <= 0 || budget_bytes < 0)
         return fae_fail(ctx, FAE_EINVAL, "fae_choose_cutoff: null or non-positive argument");
     if (!ws || ws_bytes < fae_choose_cutoff_workspace_bytes(tables))
         return fae_fail(ctx, FAE_ENOSPC, "fae_choose_cutoff: workspace too small");
@@ -345,7 +345,7 @@ extern "C" int32_t fae_choose_cutoff(fae_ctx *ctx, const fae_tables *tables, con
         small[z] = tables->h_rows[z] * row_bytes < small_table_bytes;
     }
     auto H_of = [&](int z, uint64_t c) -> uint64_t {
-        return small[z] ? 0ull : scaled_cutoff(c, (uint64_t)h_T[z], (uint64_t)n_profile_samples);
+        return small[z] ? 0ull : scaled_cutoff(c, (uint64_t)h_T[z], (uint64_t)t_denom);
     };
     Window w{ctx, tables, h_counts, (uint32_t *)ws, {}, {}};
     uint32_t lo0[FAE_MAX_TABLES] = {0};
@@ -401,7 +401,7 @@ extern "C" int32_t fae_choose_cutoff(fae_ctx *ctx, const fae_tables *tables, con
         if (small[z] || h_T[z] == 0)
             continue;
         // smallest c with H_z(c) > maxc[z]
-        unsigned __int128 need = ((unsigned __int128)(maxc[z] + 1ull) * (uint64_t)n_profile_samples + h_T[z] - 1) /
+        unsigned __int128 need = ((unsigned __int128)(maxc[z] + 1ull) * (uint64_t)t_denom + h_T[z] - 1) /
                                  (uint64_t)h_T[z];
         uint64_t cz = (uint64_t)need + 1;
         if (cz > hi_c)

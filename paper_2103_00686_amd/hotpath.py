@@ -107,8 +107,9 @@ class HotPath:
     # -- a2 -------------------------------------------------------------------------
     def choose_cutoff(self, budget_bytes: int, small_table_bytes: int = 1 << 20):
         ws = self._workspace("cut", B.fae_choose_cutoff_workspace_bytes(self.tables))
+        # threshold grid: one step of c = one access for the most-accessed table
         return B.fae_choose_cutoff(self.ctx, self.tables, self.counts, self.profiled_lookups,
-                                   self.profiled_samples, budget_bytes, small_table_bytes, ws)
+                                   max(max(self.profiled_lookups), 1), budget_bytes, small_table_bytes, ws)
 
     def count_hot(self, cutoff: Sequence[int]) -> List[int]:
         ws = self._workspace("cut", B.fae_choose_cutoff_workspace_bytes(self.tables))

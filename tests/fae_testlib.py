@@ -60,8 +60,8 @@ def oracle_hot_rule(w: S.Workload, cnts, chunks):
         H = [w.cutoff] * w.n_tables
         return H, [O.count_hot(c, w.cutoff) for c in cnts], None
     T = [sum(ch.n_lookups[z] for ch in chunks) for z in range(w.n_tables)]
-    n_prof = sum(ch.n_samples for ch in chunks)
-    c, H, nh = O.budget_cutoff(w.dim, cnts, T, n_prof, w.budget_bytes, w.small_table_bytes)
+    t_denom = max(max(T), 1)     # one step of c = one access for the most-accessed table
+    c, H, nh = O.budget_cutoff(w.dim, cnts, T, t_denom, w.budget_bytes, w.small_table_bytes)
     return [int(h) for h in H], [int(n) for n in nh], c
 
 

@@ -134,7 +134,7 @@ def test_budget_cutoff_zero_means_every_row_hot():
 
 
 def test_budget_cutoff_one_hot_threshold_equals_c():
-    # one-hot table: T_z == n_profile_samples, so H_z == c
+    # one-hot table: T_z == t_denom (the number of profiled samples), so H_z == c
     rng = np.random.default_rng(4)
     cnt = rng.poisson(2.0, 4000).astype(np.uint32)
     T = int(cnt.sum())
