@@ -39,6 +39,8 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--cpu-seconds", type=float, default=10.0)
     ap.add_argument("--set", action="append", default=[], help="library option name=value (ablation)")
+    ap.add_argument("--presort", action="store_true",
+                    help="start the backward's sort on the side stream before the forward (overlap)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -141,7 +143,7 @@ def main():
     outs = [torch.empty((hb.n_samples, nt, D), dtype=torch.float32, device=dev) for hb in batches]
     ws_need = max(B.fae_bwd_workspace_bytes(hp.hot_tables, hb.n_samples, hb.n_lookups) for hb in batches)
     hp._workspace("bwd", ws_need)
-    steps_fn = [hp.prepare_step(hb, g, o, w.lr) for hb, g, o in zip(batches, gouts, outs)]
+    steps_fn = [hp.prepare_step(hb, g, o, w.lr, presort=args.presort) for hb, g, o in zip(batches, gouts, outs)]
 
     # accounting per batch: lookups, bags, distinct rows
     acct = []

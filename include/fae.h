@@ -195,6 +195,15 @@ int32_t fae_embbag_fwd(fae_ctx *ctx, const fae_tables *hot_tables, const float *
  * not written.  dbg may be NULL.  Asynchronous. */
 size_t fae_bwd_workspace_bytes(const fae_tables *hot_tables, int64_t n_samples,
                                const int64_t *h_n_lookups);
+/* Optional: start the sort of the backward (steps that depend only on the batch, not on
+ * the gradient) on the context's side stream, so that it overlaps whatever runs on the
+ * main stream between this call and fae_embbag_bwd_sgd (the forward, the dense layers).
+ * It starts after all work queued on the main stream so far.  A following
+ * fae_embbag_bwd_sgd with the same batch and workspace waits for it and skips its own
+ * sort; with any other batch or workspace it waits and sorts itself.  The batch and the
+ * workspace must stay untouched in between.  Asynchronous. */
+int32_t fae_embbag_bwd_presort(fae_ctx *ctx, const fae_tables *hot_tables, const fae_batch *hot_batch,
+                               void *ws, size_t ws_bytes);
 int32_t fae_embbag_bwd_sgd(fae_ctx *ctx, const fae_tables *hot_tables, float *const *h_hotW,
                            const fae_batch *hot_batch, const float *gout, int64_t gout_row_stride,
                            float lr, const fae_bwd_debug *dbg, void *ws, size_t ws_bytes);

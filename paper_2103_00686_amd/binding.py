@@ -24,7 +24,8 @@ EXPORTS = [
     "fae_timing_enable", "fae_timing_reset", "fae_timing_read", "fae_kernel_name",
     "fae_profile", "fae_choose_cutoff_workspace_bytes", "fae_choose_cutoff", "fae_count_hot",
     "fae_build_workspace_bytes", "fae_build_hot_tables", "fae_partition_workspace_bytes",
-    "fae_partition_batch", "fae_embbag_fwd", "fae_bwd_workspace_bytes", "fae_embbag_bwd_sgd",
+    "fae_partition_batch", "fae_embbag_fwd", "fae_bwd_workspace_bytes", "fae_embbag_bwd_presort",
+    "fae_embbag_bwd_sgd",
 ]
 
 
@@ -295,6 +296,12 @@ def fae_bwd_workspace_bytes(hot_tables: Tables, n_samples: int, n_lookups: Seque
     t = hot_tables.c()
     nl = (C.c_int64 * len(n_lookups))(*[int(n) for n in n_lookups])
     return int(load().fae_bwd_workspace_bytes(C.byref(t), C.c_int64(n_samples), nl))
+
+
+def fae_embbag_bwd_presort(ctx: Context, hot_tables: Tables, hot_batch: Batch, ws: torch.Tensor):
+    t, b = hot_tables.c(), hot_batch.c()
+    ctx.check(load().fae_embbag_bwd_presort(ctx._h, C.byref(t), C.byref(b), _ptr(ws, torch.uint8),
+                                            C.c_size_t(ws.numel())))
 
 
 def fae_embbag_bwd_sgd(ctx: Context, hot_tables: Tables, hotW: List[torch.Tensor], hot_batch: Batch,

@@ -767,69 +767,71 @@ extern "C" size_t fae_bwd_workspace_bytes(const fae_tables *hot_tables, int64_t 
     return w.used + 256;
 }
 
-extern "C" int32_t fae_embbag_bwd_sgd(fae_ctx *ctx, const fae_tables *hot_tables, float *const *h_hotW,
-                                      const fae_batch *hot_batch, const float *gout, int64_t gout_row_stride,
-                                      float lr, const fae_bwd_debug *dbg, void *ws, size_t ws_bytes)
+namespace {
+// Common set-up of the backward: validation, workspace carving, per-table descriptors.
+struct BwdSetup {
+    BwdPlan plan;
+    BwdWs w;
+    BwdArgs a;
+    bool empty;
+};
+
+int32_t bwd_setup(fae_ctx *ctx, const fae_tables *hot_tables, const fae_batch *hot_batch, void *ws, size_t ws_bytes,
+                  const char *who, BwdSetup *out)
 {
-    int32_t rc = fae_check_tables(ctx, hot_tables, "fae_embbag_bwd_sgd");
+    int32_t rc = fae_check_tables(ctx, hot_tables, who);
     if (rc != FAE_OK)
         return rc;
-    rc = fae_check_batch(ctx, hot_tables, hot_batch, "fae_embbag_bwd_sgd");
+    rc = fae_check_batch(ctx, hot_tables, hot_batch, who);
     if (rc != FAE_OK)
         return rc;
     const int nt = hot_tables->n_tables, dim = hot_tables->dim;
-    if (dbg && !dbg->table_start)
-        return fae_fail(ctx, FAE_EINVAL, "fae_embbag_bwd_sgd: incomplete debug outputs");
-    const int64_t S = hot_batch->n_samples;
-    const BwdPlan plan = bwd_plan(nt, hot_batch->h_n_lookups);
-    if (plan.N >= 2147483647LL - SORT_TILE)
-        return fae_fail(ctx, FAE_EINVAL, "fae_embbag_bwd_sgd: more than 2^31 lookups in one call");
-    FAE_HIP(ctx, hipSetDevice(ctx->device));
-    if (plan.N == 0 || S == 0) { // nothing to update
-        if (dbg) {
-            rc = fae_fill_u32(ctx, dbg->table_start, nt + 1, 0u);
-            if (rc != FAE_OK)
-                return rc;
-        }
+    out->plan = bwd_plan(nt, hot_batch->h_n_lookups);
+    if (out->plan.N >= 2147483647LL - SORT_TILE)
+        return fae_fail(ctx, FAE_EINVAL, "%s: more than 2^31 lookups in one call", who);
+    out->empty = out->plan.N == 0 || hot_batch->n_samples == 0;
+    if (out->empty)
         return FAE_OK;
-    }
-    if (!h_hotW || !gout || gout_row_stride < (int64_t)nt * dim)
-        return fae_fail(ctx, FAE_EINVAL, "fae_embbag_bwd_sgd: null gradient/weights or gout_row_stride < n_tables*dim");
-    if (dbg && (!dbg->uniq || !dbg->runlen))
-        return fae_fail(ctx, FAE_EINVAL, "fae_embbag_bwd_sgd: incomplete debug outputs");
     if (!ws)
-        return fae_fail(ctx, FAE_ENOSPC, "fae_embbag_bwd_sgd: null workspace");
-    const int span = bwd_span(plan, ctx->n_cu);
-    BwdWs w = bwd_carve(ws, ws_bytes, plan, nt, dim, BWD_SPAN_MIN);
-    if (!w.ok)
-        return fae_fail(ctx, FAE_ENOSPC, "fae_embbag_bwd_sgd: workspace too small (%zu needed)", w.used);
-
-    BwdArgs a;
+        return fae_fail(ctx, FAE_ENOSPC, "%s: null workspace", who);
+    out->w = bwd_carve(ws, ws_bytes, out->plan, nt, dim, BWD_SPAN_MIN);
+    if (!out->w.ok)
+        return fae_fail(ctx, FAE_ENOSPC, "%s: workspace too small (%zu needed)", who, out->w.used);
+    BwdArgs &a = out->a;
     memset(&a, 0, sizeof(a));
-    bool vec = (dim % 4 == 0) && (gout_row_stride % 4 == 0) && (((uintptr_t)gout) % 16 == 0);
-    int64_t lookups = 0, tiles = 0;
+    int64_t lookups = 0;
     for (int z = 0; z < nt; ++z) {
-        if (!h_hotW[z] && hot_tables->h_rows[z] > 0)
-            return fae_fail(ctx, FAE_EINVAL, "fae_embbag_bwd_sgd: null weights for table %d", z);
-        a.W[z] = h_hotW[z];
         a.slots[z] = hot_batch->h_indices[z];
         a.offsets[z] = hot_batch->h_offsets ? hot_batch->h_offsets[z] : nullptr;
         a.n_hot[z] = (int32_t)hot_tables->h_rows[z];
-        if (((uintptr_t)h_hotW[z]) % 16 != 0)
-            vec = false;
         a.seg_start[z] = (int32_t)lookups;
-        a.tile_start[z] = (int32_t)tiles;
         lookups += hot_batch->h_n_lookups[z];
-        tiles += (hot_batch->h_n_lookups[z] + SORT_TILE - 1) / SORT_TILE;
     }
     a.seg_start[nt] = (int32_t)lookups;
-    a.tile_start[nt] = (int32_t)tiles;
+    a.n_tables = nt;
+    a.dim = dim;
+    a.n_samples = (int32_t)hot_batch->n_samples;
+    a.hist = out->w.hist;
+    a.tot = out->w.tot;
+    a.partial = out->w.partial;
+    a.status = ctx->d_block;
+    return FAE_OK;
+}
+
+// Steps 1 + 2 on stream `st`: (slot, sample) pairs sorted by slot per table.  *cur_out names
+// the ping-pong buffer that holds the result.
+int32_t bwd_sort_stage(fae_ctx *ctx, hipStream_t st, const fae_tables *hot_tables, const fae_batch *hot_batch,
+                       BwdSetup &su, int *cur_out)
+{
+    BwdArgs &a = su.a;
+    const BwdWs &w = su.w;
+    const int nt = hot_tables->n_tables;
     // Tables whose lookups fit one workgroup are sorted in LDS; they take no part in the
     // global passes (zero tiles, zero key blocks).
     bool in_lds[FAE_MAX_TABLES];
     int n_lds = 0;
     int64_t max_hot_global = 0;
-    tiles = 0;
+    int64_t tiles = 0;
     for (int z = 0; z < nt; ++z) {
         const int64_t nl = hot_batch->h_n_lookups[z];
         in_lds[z] = ctx->opt_sort != 1 && nl > 0 && nl <= LSORT_MAX;
@@ -842,18 +844,6 @@ extern "C" int32_t fae_embbag_bwd_sgd(fae_ctx *ctx, const fae_tables *hot_tables
             tiles += (nl + SORT_TILE - 1) / SORT_TILE;
     }
     a.tile_start[nt] = (int32_t)tiles;
-    a.n_tables = nt;
-    a.dim = dim;
-    a.n_samples = (int32_t)S;
-    a.hist = w.hist;
-    a.tot = w.tot;
-    a.gout = gout;
-    a.gout_stride = gout_row_stride;
-    a.lr = lr;
-    a.partial = w.partial;
-    a.span = span;
-    a.status = ctx->d_block;
-
     // 1. keys
     {
         int64_t blocks = 0;
@@ -866,8 +856,8 @@ extern "C" int32_t fae_embbag_bwd_sgd(fae_ctx *ctx, const fae_tables *hot_tables
         a.keys_in = w.keys[0];
         a.vals_in = w.vals[0];
         if (blocks > 0) {
-            fae_ktimer kt(ctx, FAE_K_BWD_KEYS);
-            hipLaunchKernelGGL(bwd_keys_kernel, dim3((unsigned)blocks), dim3(256), 0, ctx->stream, a);
+            fae_ktimer kt(ctx, FAE_K_BWD_KEYS, st);
+            hipLaunchKernelGGL(bwd_keys_kernel, dim3((unsigned)blocks), dim3(256), 0, st, a);
             FAE_LAUNCH_CHECK(ctx);
         }
     }
@@ -886,18 +876,18 @@ extern "C" int32_t fae_embbag_bwd_sgd(fae_ctx *ctx, const fae_tables *hot_tables
         a.keys_out = w.keys[cur ^ 1];
         a.vals_out = w.vals[cur ^ 1];
         {
-            fae_ktimer kt(ctx, FAE_K_SORT_HIST);
-            hipLaunchKernelGGL(sort_hist_kernel, dim3((unsigned)tiles), dim3(SORT_THREADS), 0, ctx->stream, a);
+            fae_ktimer kt(ctx, FAE_K_SORT_HIST, st);
+            hipLaunchKernelGGL(sort_hist_kernel, dim3((unsigned)tiles), dim3(SORT_THREADS), 0, st, a);
             FAE_LAUNCH_CHECK(ctx);
         }
         {
-            fae_ktimer kt(ctx, FAE_K_SORT_COLSCAN);
-            hipLaunchKernelGGL(sort_colscan_kernel, dim3((unsigned)((nt * RADIX + 3) / 4)), dim3(256), 0, ctx->stream, a);
+            fae_ktimer kt(ctx, FAE_K_SORT_COLSCAN, st);
+            hipLaunchKernelGGL(sort_colscan_kernel, dim3((unsigned)((nt * RADIX + 3) / 4)), dim3(256), 0, st, a);
             FAE_LAUNCH_CHECK(ctx);
         }
         {
-            fae_ktimer kt(ctx, FAE_K_SORT_SCATTER);
-            hipLaunchKernelGGL(sort_scatter_kernel, dim3((unsigned)tiles), dim3(SORT_THREADS), 0, ctx->stream, a);
+            fae_ktimer kt(ctx, FAE_K_SORT_SCATTER, st);
+            hipLaunchKernelGGL(sort_scatter_kernel, dim3((unsigned)tiles), dim3(SORT_THREADS), 0, st, a);
             FAE_LAUNCH_CHECK(ctx);
         }
         cur ^= 1;
@@ -944,10 +934,104 @@ extern "C" int32_t fae_embbag_bwd_sgd(fae_ctx *ctx, const fae_tables *hot_tables
         la.keys_out = w.keys[cur];
         la.vals_out = w.vals[cur];
         la.status = ctx->d_block;
-        fae_ktimer kt(ctx, FAE_K_LDS_SORT);
-        hipLaunchKernelGGL(lds_sort_kernel, dim3(nb), dim3(LSORT_THREADS), 0, ctx->stream, la);
+        fae_ktimer kt(ctx, FAE_K_LDS_SORT, st);
+        hipLaunchKernelGGL(lds_sort_kernel, dim3(nb), dim3(LSORT_THREADS), 0, st, la);
         FAE_LAUNCH_CHECK(ctx);
     }
+    *cur_out = cur;
+    return FAE_OK;
+}
+} // namespace
+
+extern "C" int32_t fae_embbag_bwd_presort(fae_ctx *ctx, const fae_tables *hot_tables, const fae_batch *hot_batch,
+                                          void *ws, size_t ws_bytes)
+{
+    BwdSetup su;
+    int32_t rc = bwd_setup(ctx, hot_tables, hot_batch, ws, ws_bytes, "fae_embbag_bwd_presort", &su);
+    if (rc != FAE_OK)
+        return rc;
+    ctx->presort.valid = false;
+    if (su.empty)
+        return FAE_OK;
+    FAE_HIP(ctx, hipSetDevice(ctx->device));
+    // fork: the side stream starts after everything already queued on the main stream
+    // (earlier users of this workspace, producers of the slots)
+    FAE_HIP(ctx, hipEventRecord(ctx->ev_fork, ctx->stream));
+    FAE_HIP(ctx, hipStreamWaitEvent(ctx->aux_stream, ctx->ev_fork, 0));
+    int cur = 0;
+    rc = bwd_sort_stage(ctx, ctx->aux_stream, hot_tables, hot_batch, su, &cur);
+    if (rc != FAE_OK)
+        return rc;
+    FAE_HIP(ctx, hipEventRecord(ctx->ev_join, ctx->aux_stream));
+    ctx->presort.valid = true;
+    ctx->presort.ws = ws;
+    ctx->presort.first_indices = hot_batch->h_indices[0];
+    ctx->presort.n_samples = hot_batch->n_samples;
+    ctx->presort.n_lookups = su.plan.N;
+    ctx->presort.cur = cur;
+    return FAE_OK;
+}
+
+extern "C" int32_t fae_embbag_bwd_sgd(fae_ctx *ctx, const fae_tables *hot_tables, float *const *h_hotW,
+                                      const fae_batch *hot_batch, const float *gout, int64_t gout_row_stride,
+                                      float lr, const fae_bwd_debug *dbg, void *ws, size_t ws_bytes)
+{
+    if (dbg && !dbg->table_start)
+        return fae_fail(ctx, FAE_EINVAL, "fae_embbag_bwd_sgd: incomplete debug outputs");
+    BwdSetup su;
+    int32_t rc = bwd_setup(ctx, hot_tables, hot_batch, ws, ws_bytes, "fae_embbag_bwd_sgd", &su);
+    if (rc != FAE_OK)
+        return rc;
+    const int nt = hot_tables->n_tables, dim = hot_tables->dim;
+    FAE_HIP(ctx, hipSetDevice(ctx->device));
+    if (su.empty) { // nothing to update
+        if (dbg) {
+            rc = fae_fill_u32(ctx, dbg->table_start, nt + 1, 0u);
+            if (rc != FAE_OK)
+                return rc;
+        }
+        return FAE_OK;
+    }
+    if (!h_hotW || !gout || gout_row_stride < (int64_t)nt * dim)
+        return fae_fail(ctx, FAE_EINVAL, "fae_embbag_bwd_sgd: null gradient/weights or gout_row_stride < n_tables*dim");
+    if (dbg && (!dbg->uniq || !dbg->runlen))
+        return fae_fail(ctx, FAE_EINVAL, "fae_embbag_bwd_sgd: incomplete debug outputs");
+    const BwdPlan &plan = su.plan;
+    const BwdWs &w = su.w;
+    BwdArgs &a = su.a;
+    const int span = bwd_span(plan, ctx->n_cu);
+    bool vec = (dim % 4 == 0) && (gout_row_stride % 4 == 0) && (((uintptr_t)gout) % 16 == 0);
+    for (int z = 0; z < nt; ++z) {
+        if (!h_hotW[z] && hot_tables->h_rows[z] > 0)
+            return fae_fail(ctx, FAE_EINVAL, "fae_embbag_bwd_sgd: null weights for table %d", z);
+        a.W[z] = h_hotW[z];
+        if (((uintptr_t)h_hotW[z]) % 16 != 0)
+            vec = false;
+    }
+    a.gout = gout;
+    a.gout_stride = gout_row_stride;
+    a.lr = lr;
+    a.span = span;
+
+    // 1 + 2. sorted (slot, sample) pairs: take them from a matching presort, or sort now
+    int cur = 0;
+    if (ctx->presort.valid) {
+        // whatever the side stream was asked to do must be finished before this workspace is used
+        FAE_HIP(ctx, hipStreamWaitEvent(ctx->stream, ctx->ev_join, 0));
+    }
+    if (ctx->presort.valid && ctx->presort.ws == ws && ctx->presort.first_indices == hot_batch->h_indices[0] &&
+        ctx->presort.n_samples == hot_batch->n_samples && ctx->presort.n_lookups == plan.N) {
+        cur = ctx->presort.cur;
+    } else {
+        rc = bwd_sort_stage(ctx, ctx->stream, hot_tables, hot_batch, su, &cur);
+        if (rc != FAE_OK)
+            return rc;
+    }
+    ctx->presort.valid = false;
+    a.keys_in = w.keys[cur];
+    a.vals_in = w.vals[cur];
+    a.keys_out = nullptr;
+    a.vals_out = nullptr;
 
     // 3 + 4. reduce + SGD, then the runs that cross span borders
     const int ncols = vec ? dim / 4 : dim;

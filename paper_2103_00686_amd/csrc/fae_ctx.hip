@@ -58,6 +58,14 @@ extern "C" int32_t fae_create(fae_ctx **out, int32_t device, void *hip_stream)
         return FAE_EHIP;
     }
     memset(ctx->h_block, 0, FAE_BLK_WORDS * sizeof(uint32_t));
+    if (hipStreamCreateWithFlags(&ctx->aux_stream, hipStreamNonBlocking) != hipSuccess ||
+        hipEventCreateWithFlags(&ctx->ev_fork, hipEventDisableTiming) != hipSuccess ||
+        hipEventCreateWithFlags(&ctx->ev_join, hipEventDisableTiming) != hipSuccess) {
+        (void)hipFree(ctx->d_block);
+        (void)hipHostFree(ctx->h_block);
+        delete ctx;
+        return FAE_EHIP;
+    }
     hipLaunchKernelGGL(fae_clear_words_kernel, dim3(FAE_BLK_WORDS / 256), dim3(256), 0, ctx->stream,
                        ctx->d_block, FAE_BLK_WORDS);
     if (hipGetLastError() != hipSuccess || hipStreamSynchronize(ctx->stream) != hipSuccess) {
@@ -76,6 +84,14 @@ extern "C" void fae_destroy(fae_ctx *ctx)
         return;
     (void)hipSetDevice(ctx->device);
     (void)hipStreamSynchronize(ctx->stream);
+    if (ctx->aux_stream) {
+        (void)hipStreamSynchronize(ctx->aux_stream);
+        (void)hipStreamDestroy(ctx->aux_stream);
+    }
+    if (ctx->ev_fork)
+        (void)hipEventDestroy(ctx->ev_fork);
+    if (ctx->ev_join)
+        (void)hipEventDestroy(ctx->ev_join);
     for (const fae_timed_launch &t : ctx->timed) {
         (void)hipEventDestroy(t.e0);
         (void)hipEventDestroy(t.e1);
@@ -103,7 +119,9 @@ static hipEvent_t take_event(fae_ctx *c)
     return e;
 }
 
-fae_ktimer::fae_ktimer(fae_ctx *ctx, int id) : c(ctx), on(false)
+fae_ktimer::fae_ktimer(fae_ctx *ctx, int id) : fae_ktimer(ctx, id, ctx ? ctx->stream : nullptr) {}
+
+fae_ktimer::fae_ktimer(fae_ctx *ctx, int id, hipStream_t stream) : c(ctx), on(false), st(stream)
 {
     t.id = id;
     t.e0 = t.e1 = nullptr;
@@ -113,20 +131,21 @@ fae_ktimer::fae_ktimer(fae_ctx *ctx, int id) : c(ctx), on(false)
     t.e1 = take_event(ctx);
     if (!t.e0 || !t.e1)
         return;
-    on = hipEventRecord(t.e0, ctx->stream) == hipSuccess;
+    on = hipEventRecord(t.e0, st) == hipSuccess;
 }
 
 fae_ktimer::~fae_ktimer()
 {
     if (!on)
         return;
-    if (hipEventRecord(t.e1, c->stream) == hipSuccess)
+    if (hipEventRecord(t.e1, st) == hipSuccess)
         c->timed.push_back(t);
 }
 
 static int32_t timing_collect(fae_ctx *ctx)
 {
     FAE_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    FAE_HIP(ctx, hipStreamSynchronize(ctx->aux_stream));
     for (const fae_timed_launch &t : ctx->timed) {
         float ms = 0.f;
         if (hipEventElapsedTime(&ms, t.e0, t.e1) == hipSuccess) {
@@ -211,6 +230,8 @@ int32_t fae_readback(fae_ctx *ctx, int first, int n)
 
 int32_t fae_sync_status(fae_ctx *ctx)
 {
+    if (ctx->aux_stream)
+        FAE_HIP(ctx, hipStreamSynchronize(ctx->aux_stream));
     int32_t rc = fae_readback(ctx, FAE_BLK_STATUS, 1);
     if (rc != FAE_OK)
         return rc;

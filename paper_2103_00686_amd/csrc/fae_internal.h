@@ -37,6 +37,16 @@ struct fae_ctx {
     int64_t opt_sort = 0;    // 0 auto, 1 global radix, 2 LDS per table
     int64_t opt_fwd_stream = 1; // non-temporal stores for the pooled output
     char err[512] = {0};
+    // side stream for work that may overlap the main stream (backward presort)
+    hipStream_t aux_stream = nullptr;
+    hipEvent_t ev_fork = nullptr, ev_join = nullptr;
+    struct {
+        bool valid = false;
+        const void *ws = nullptr;
+        const void *first_indices = nullptr;
+        int64_t n_samples = 0, n_lookups = 0;
+        int cur = 0;
+    } presort;
     // per-kernel timing
     bool timing = false;
     std::vector<fae_timed_launch> timed;  // launches recorded since the last read
@@ -50,7 +60,9 @@ struct fae_ktimer {
     fae_ctx *c;
     fae_timed_launch t;
     bool on;
+    hipStream_t st;
     fae_ktimer(fae_ctx *ctx, int id);
+    fae_ktimer(fae_ctx *ctx, int id, hipStream_t stream);
     ~fae_ktimer();
 };
 

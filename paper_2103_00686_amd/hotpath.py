@@ -72,9 +72,11 @@ class HotPath:
             t = self._hot_tables = B.Tables(list(self.n_hot), self.dim)
         return t
 
-    def prepare_step(self, hb: HotBatch, gout: torch.Tensor, out: torch.Tensor, lr: float):
+    def prepare_step(self, hb: HotBatch, gout: torch.Tensor, out: torch.Tensor, lr: float, presort: bool = True):
         """Pre-marshalled forward + backward/SGD on one hot batch: returns a zero-argument
-        callable that only issues the two library calls (for tight training loops)."""
+        callable that only issues the library calls (for tight training loops).  With
+        ``presort`` the backward's sort is started on the side stream first, so it overlaps
+        the forward."""
         import ctypes as C
         lib = B.load()
         t, b = self.hot_tables.c(), hb.batch().c()
@@ -87,7 +89,9 @@ class HotPath:
         keep = (t, b, wptr, ws, out, gout, hb)
 
         def step():
-            rc = lib.fae_embbag_fwd(h, tr, wptr, br, a_out, stride)
+            rc = lib.fae_embbag_bwd_presort(h, tr, br, a_ws, n_ws) if presort else 0
+            if rc == 0:
+                rc = lib.fae_embbag_fwd(h, tr, wptr, br, a_out, stride)
             if rc == 0:
                 rc = lib.fae_embbag_bwd_sgd(h, tr, wptr, br, a_gout, stride, c_lr, None, a_ws, n_ws)
             if rc != 0:
@@ -155,6 +159,9 @@ class HotPath:
     # -- a7 + a8 --------------------------------------------------------------------
     def bwd_workspace(self, hb: HotBatch) -> torch.Tensor:
         return self._workspace("bwd", B.fae_bwd_workspace_bytes(self.hot_tables, hb.n_samples, hb.n_lookups))
+
+    def presort(self, hb: HotBatch):
+        B.fae_embbag_bwd_presort(self.ctx, self.hot_tables, hb.batch(), self.bwd_workspace(hb))
 
     def backward_sgd(self, hb: HotBatch, gout: torch.Tensor, lr: float, debug: bool = False):
         ws = self.bwd_workspace(hb)

@@ -156,8 +156,12 @@ class Pipeline:
         return out
 
     # a7 + a8
-    def check_backward(self, hb: HotBatch, stream: int):
+    def check_backward(self, hb: HotBatch, stream: int, presort: Optional[HotBatch] = None):
+        """presort: start the backward's sort for that batch on the side stream first (the same
+        batch: the sorted pairs are reused; another batch: they must be ignored)."""
         w = self.w
+        if presort is not None:
+            self.hp.presort(presort)
         gout = S.upstream_grads(w, stream, hb.n_samples)
         before = [x.clone() for x in self.hp.hotW]      # device-side snapshot of the library's own state
         dbg = self.hp.backward_sgd(hb, gout.to(self.dev), w.lr, debug=True)

@@ -37,8 +37,8 @@ def test_workload_end_to_end(dev, cfg_id, materialise):
     p.check_forward(batches[0])
     p.check_backward(batches[0], stream=20)
     p.check_forward(batches[-1], exact_gather=False)           # sees the updated rows
-    p.check_backward(batches[-1], stream=21)                   # in-place state carried over
-    p.check_backward(batches[0], stream=22)
+    p.check_backward(batches[-1], stream=21, presort=batches[-1])   # in-place state carried over; sort on the side stream
+    p.check_backward(batches[0], stream=22, presort=batches[-1])    # a presort of another batch is not used
 
 
 @pytest.mark.parametrize("variant", [1, 2])
