@@ -219,6 +219,23 @@ def main():
                 "per_lookup_GBps": round(per_lookup_bytes / (ms_per_step * 1e-3) / 1e9, 1),
                 "kernels_us_per_step": {k: round(v["us_per_step"], 2) for k, v in kern.items()}}
 
+    # ---- what a plain streaming copy reaches on this device (1 GiB read + 1 GiB write) ------
+    src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+    dst = torch.empty_like(src)
+    for _ in range(3):
+        B.fae_copy_probe(hp.ctx, dst, src)
+    B.fae_timing_enable(hp.ctx, True)
+    B.fae_timing_reset(hp.ctx)
+    for _ in range(10):
+        B.fae_copy_probe(hp.ctx, dst, src)
+    ms, n = B.fae_timing_read(hp.ctx, 13)
+    B.fae_timing_enable(hp.ctx, False)
+    copy_gbps = 2 * src.numel() * 4 / (ms / n * 1e-3) / 1e9
+    roofline["copy_ceiling_GBps"] = round(copy_gbps, 1)
+    roofline["frac_of_copy_ceiling"] = round(dom_gbps / copy_gbps, 4)
+    roofline["step_frac_of_copy_ceiling"] = round((bytes_fwd + bytes_bwd) / (ms_per_step * 1e-3) / 1e9 / copy_gbps, 4)
+    del src, dst
+
     # ---- the oracle on the host, bounded sample ----------------------------------------
     cpu = None
     if not args.no_cpu:

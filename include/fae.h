@@ -117,11 +117,16 @@ int32_t fae_set_option(fae_ctx *ctx, const char *name, int64_t value);
 #define FAE_K_PARTITION 10   /* input classifier kernels                        */
 #define FAE_K_BUILD 11       /* classify / scan / gather                        */
 #define FAE_K_OTHER 12
-#define FAE_K_COUNT 13
+#define FAE_K_COPY_PROBE 13  /* plain streaming copy (bandwidth ceiling, counter calibration) */
+#define FAE_K_COUNT 14
 int32_t fae_timing_enable(fae_ctx *ctx, int32_t on);
 int32_t fae_timing_reset(fae_ctx *ctx);
 int32_t fae_timing_read(fae_ctx *ctx, int32_t kernel_class, double *h_total_ms, int64_t *h_launches);
 const char *fae_kernel_name(int32_t kernel_class);
+/* Plain device-to-device streaming copy of `bytes` (multiple of 16) by a 16-byte-per-lane
+ * kernel: what a bandwidth-bound kernel can reach on this device, and a transfer of known
+ * size against which hardware byte counters are scaled.  Asynchronous. */
+int32_t fae_copy_probe(fae_ctx *ctx, void *dst, const void *src, size_t bytes);
 
 /* ---- a1: Embedding Logger (Sec. 4.1.2) ------------------------------------- */
 /* counts_z[r] += number of lookups of `chunk` into row r of table z.  The caller

@@ -21,7 +21,7 @@ FAE_SRC_DEVICE, FAE_SRC_PROCEDURAL = 0, 1
 
 EXPORTS = [
     "fae_create", "fae_destroy", "fae_last_error", "fae_version", "fae_sync", "fae_set_option",
-    "fae_timing_enable", "fae_timing_reset", "fae_timing_read", "fae_kernel_name",
+    "fae_timing_enable", "fae_timing_reset", "fae_timing_read", "fae_kernel_name", "fae_copy_probe",
     "fae_profile", "fae_choose_cutoff_workspace_bytes", "fae_choose_cutoff", "fae_count_hot",
     "fae_build_workspace_bytes", "fae_build_hot_tables", "fae_partition_workspace_bytes",
     "fae_partition_batch", "fae_embbag_fwd", "fae_bwd_workspace_bytes", "fae_embbag_bwd_presort",
@@ -183,7 +183,7 @@ def fae_set_option(ctx: Context, name: str, value: int):
     ctx.check(load().fae_set_option(ctx._h, name.encode(), C.c_int64(value)))
 
 
-FAE_K_COUNT = 13
+FAE_K_COUNT = 14
 
 
 def fae_kernel_name(kernel_class: int) -> str:
@@ -203,6 +203,12 @@ def fae_timing_read(ctx: Context, kernel_class: int):
     ms, n = C.c_double(0.0), C.c_int64(0)
     ctx.check(load().fae_timing_read(ctx._h, C.c_int32(kernel_class), C.byref(ms), C.byref(n)))
     return float(ms.value), int(n.value)
+
+
+def fae_copy_probe(ctx: Context, dst: torch.Tensor, src: torch.Tensor):
+    assert dst.numel() * dst.element_size() == src.numel() * src.element_size()
+    ctx.check(load().fae_copy_probe(ctx._h, C.c_void_p(dst.data_ptr()), C.c_void_p(src.data_ptr()),
+                                    C.c_size_t(src.numel() * src.element_size())))
 
 
 def fae_profile(ctx: Context, tables: Tables, chunk: Batch, counts: List[torch.Tensor]):

@@ -63,24 +63,82 @@ struct BwdArgs {
 // ---------------------------------------------------------------------------------
 // 1. keys
 // ---------------------------------------------------------------------------------
+#define KEYS_PER_THREAD 4
+#define KEYS_PER_BLOCK (256 * KEYS_PER_THREAD)
+
+// Each thread handles four consecutive lookups (16-byte loads and stores when aligned).
 __global__ __launch_bounds__(256) void bwd_keys_kernel(BwdArgs a)
 {
     const int z = fae_find_table(a.blk_start, a.n_tables, blockIdx.x);
-    const int j = (blockIdx.x - a.blk_start[z]) * 256 + threadIdx.x;
+    const int j0 = (blockIdx.x - a.blk_start[z]) * KEYS_PER_BLOCK + threadIdx.x * KEYS_PER_THREAD;
     const int n = a.seg_start[z + 1] - a.seg_start[z];
-    if (j >= n)
-        return;
     const int32_t *off = a.offsets[z];
-    int s = off ? fae_sample_of(off, a.n_samples, j) : j;
-    int k = a.slots[z][j];
-    if ((unsigned)k >= (unsigned)a.n_hot[z]) {
-        fae_flag(a.status, FAE_STATUS_ERANGE);
-        k = a.n_hot[z]; // sorts behind every valid slot of the table; never dereferenced
+    // sample of a lookup: one binary search per workgroup (its first lookup), then every thread
+    // walks forward from there (a workgroup's lookups span few bags)
+    __shared__ int s_first;
+    if (off && threadIdx.x == 0) {
+        const int jb = (blockIdx.x - a.blk_start[z]) * KEYS_PER_BLOCK;
+        s_first = fae_sample_of(off, a.n_samples, jb < n ? jb : n - 1);
     }
-    if (off && (off[s] > j || off[s + 1] <= j))
-        fae_flag(a.status, FAE_STATUS_ERANGE); // malformed CSR
-    a.keys_in[a.seg_start[z] + j] = k;
-    a.vals_in[a.seg_start[z] + j] = s;
+    if (off)
+        __syncthreads();
+    if (j0 >= n)
+        return;
+    const int32_t *slots = a.slots[z] + j0;
+    int32_t *ko = a.keys_in + a.seg_start[z] + j0;
+    int32_t *vo = a.vals_in + a.seg_start[z] + j0;
+    int k[KEYS_PER_THREAD], v[KEYS_PER_THREAD];
+    const bool full = j0 + KEYS_PER_THREAD <= n;
+    const bool aligned = full && ((((uintptr_t)slots) | ((uintptr_t)ko) | ((uintptr_t)vo)) & 15) == 0;
+    if (aligned) {
+        const int4 t = *(const int4 *)slots;
+        k[0] = t.x; k[1] = t.y; k[2] = t.z; k[3] = t.w;
+    } else {
+#pragma unroll
+        for (int q = 0; q < KEYS_PER_THREAD; ++q)
+            k[q] = j0 + q < n ? slots[q] : 0;
+    }
+    bool bad = false;
+    int s = off ? s_first : 0;
+#pragma unroll
+    for (int q = 0; q < KEYS_PER_THREAD; ++q) {
+        const int j = j0 + q;
+        if (j >= n)
+            break;
+        if ((unsigned)k[q] >= (unsigned)a.n_hot[z]) {
+            bad = true;
+            k[q] = a.n_hot[z]; // sorts behind every valid slot of the table; never dereferenced
+        }
+        if (off) {
+            // bounded walk; a long stretch of empty bags falls back to a search
+            int steps = 0;
+            while (s + 1 < a.n_samples && off[s + 1] <= j) {
+                ++s;
+                if (++steps == 64) {
+                    s = fae_sample_of(off, a.n_samples, j);
+                    break;
+                }
+            }
+            if (off[s] > j || off[s + 1] <= j)
+                bad = true; // malformed CSR
+            v[q] = s;
+        } else {
+            v[q] = j;
+        }
+    }
+    if (bad)
+        fae_flag(a.status, FAE_STATUS_ERANGE);
+    if (aligned) {
+        *(int4 *)ko = make_int4(k[0], k[1], k[2], k[3]);
+        *(int4 *)vo = make_int4(v[0], v[1], v[2], v[3]);
+    } else {
+#pragma unroll
+        for (int q = 0; q < KEYS_PER_THREAD; ++q)
+            if (j0 + q < n) {
+                ko[q] = k[q];
+                vo[q] = v[q];
+            }
+    }
 }
 
 // ---------------------------------------------------------------------------------
@@ -96,11 +154,23 @@ __global__ __launch_bounds__(SORT_THREADS) void sort_hist_kernel(BwdArgs a)
     const int base = a.seg_start[z] + tl * SORT_TILE;
     cnt[threadIdx.x] = 0;
     __syncthreads();
+    const int32_t *kp = a.keys_in + base;
+    if (base + SORT_TILE <= seg1 && (((uintptr_t)kp) & 15) == 0) {
 #pragma unroll
-    for (int i = 0; i < SORT_ITEMS; ++i) {
-        int p = base + i * SORT_THREADS + threadIdx.x;
-        if (p < seg1)
-            atomicAdd(&cnt[(a.keys_in[p] >> a.shift) & a.mask], 1);
+        for (int i = 0; i < SORT_ITEMS / 4; ++i) { // 16-byte loads; the count does not depend on the order
+            const int4 t = ((const int4 *)kp)[i * SORT_THREADS + threadIdx.x];
+            atomicAdd(&cnt[(t.x >> a.shift) & a.mask], 1);
+            atomicAdd(&cnt[(t.y >> a.shift) & a.mask], 1);
+            atomicAdd(&cnt[(t.z >> a.shift) & a.mask], 1);
+            atomicAdd(&cnt[(t.w >> a.shift) & a.mask], 1);
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < SORT_ITEMS; ++i) {
+            int p = base + i * SORT_THREADS + threadIdx.x;
+            if (p < seg1)
+                atomicAdd(&cnt[(a.keys_in[p] >> a.shift) & a.mask], 1);
+        }
     }
     __syncthreads();
     a.hist[RADIX * a.tile_start[z] + threadIdx.x * tiles_z + tl] = cnt[threadIdx.x];
@@ -129,17 +199,24 @@ __global__ __launch_bounds__(256) void sort_colscan_kernel(BwdArgs a)
         a.tot[wid] = carry;
 }
 
+// Stable scatter of one tile.  Ranks come from a wave-level match on the digit plus per-wave
+// counters; the tile is then put in digit order inside LDS so that the global writes of a
+// digit are runs of consecutive addresses instead of single scattered words.
 __global__ __launch_bounds__(SORT_THREADS) void sort_scatter_kernel(BwdArgs a)
 {
-    __shared__ int wcnt[SORT_WAVES][RADIX];
-    __shared__ int digoff[SORT_WAVES][RADIX];
+    __shared__ int wcnt[SORT_WAVES][RADIX];  // per wave: running count, then start inside the tile
+    __shared__ int gbase[RADIX];             // global position of the tile's first element of a digit
+    __shared__ int tbase[RADIX];             // position inside the tile of the first element of a digit
+    __shared__ int skey[SORT_TILE], sval[SORT_TILE];
     __shared__ int scan_lds[SORT_THREADS / FAE_WAVE + 1];
     const int z = fae_find_table(a.tile_start, a.n_tables, blockIdx.x);
     const int tl = blockIdx.x - a.tile_start[z];
     const int tiles_z = a.tile_start[z + 1] - a.tile_start[z];
     const int seg1 = a.seg_start[z + 1];
     const int w = threadIdx.x / FAE_WAVE, lane = fae_lane();
-    const int base = a.seg_start[z] + tl * SORT_TILE + w * (FAE_WAVE * SORT_ITEMS);
+    const int tile0 = a.seg_start[z] + tl * SORT_TILE;
+    const int base = tile0 + w * (FAE_WAVE * SORT_ITEMS);
+    const int n_tile = seg1 - tile0 < SORT_TILE ? seg1 - tile0 : SORT_TILE;
     volatile int *my_cnt = wcnt[w];
 #pragma unroll
     for (int i = 0; i < RADIX / FAE_WAVE; ++i)
@@ -154,6 +231,10 @@ __global__ __launch_bounds__(SORT_THREADS) void sort_scatter_kernel(BwdArgs a)
         const bool valid = p < seg1;
         key[i] = valid ? a.keys_in[p] : 0;
         val[i] = valid ? a.vals_in[p] : 0;
+    }
+#pragma unroll
+    for (int i = 0; i < SORT_ITEMS; ++i) {
+        const bool valid = base + i * FAE_WAVE + lane < seg1;
         const int d = (key[i] >> a.shift) & a.mask;
         // lanes of this round that hold the same digit (valid lanes only)
         uint64_t peers = __ballot(valid);
@@ -176,26 +257,39 @@ __global__ __launch_bounds__(SORT_THREADS) void sort_scatter_kernel(BwdArgs a)
     }
     __syncthreads();
     {
-        // thread t owns digit t: offsets of the four waves inside this tile, plus the global base
+        // thread t owns digit t: the four waves' counts -> starts inside the tile and in the output
         const int t = threadIdx.x;
-        int c0 = wcnt[0][t], c1 = wcnt[1][t], c2 = wcnt[2][t];
+        const int c0 = wcnt[0][t], c1 = wcnt[1][t], c2 = wcnt[2][t], c3 = wcnt[3][t];
         int total;
-        int ex = fae_block_excl_scan<SORT_THREADS>(a.tot[z * RADIX + t], scan_lds, &total);
-        int gb = a.seg_start[z] + ex + a.hist[RADIX * a.tile_start[z] + t * tiles_z + tl];
-        digoff[0][t] = gb;
-        digoff[1][t] = gb + c0;
-        digoff[2][t] = gb + c0 + c1;
-        digoff[3][t] = gb + c0 + c1 + c2;
+        const int ex = fae_block_excl_scan<SORT_THREADS>(a.tot[z * RADIX + t], scan_lds, &total);
+        gbase[t] = a.seg_start[z] + ex + a.hist[RADIX * a.tile_start[z] + t * tiles_z + tl];
+        const int tb = fae_block_excl_scan<SORT_THREADS>(c0 + c1 + c2 + c3, scan_lds, &total);
+        tbase[t] = tb;
+        wcnt[0][t] = tb;
+        wcnt[1][t] = tb + c0;
+        wcnt[2][t] = tb + c0 + c1;
+        wcnt[3][t] = tb + c0 + c1 + c2;
     }
     __syncthreads();
 #pragma unroll
     for (int i = 0; i < SORT_ITEMS; ++i) {
-        const int p = base + i * FAE_WAVE + lane;
-        if (p < seg1) {
+        if (base + i * FAE_WAVE + lane < seg1) {
             const int d = (key[i] >> a.shift) & a.mask;
-            const int dst = digoff[w][d] + off[i];
-            a.keys_out[dst] = key[i];
-            a.vals_out[dst] = val[i];
+            const int lp = wcnt[w][d] + off[i];
+            skey[lp] = key[i];
+            sval[lp] = val[i];
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < SORT_ITEMS; ++i) {
+        const int lp = i * SORT_THREADS + threadIdx.x;
+        if (lp < n_tile) {
+            const int k = skey[lp];
+            const int d = (k >> a.shift) & a.mask;
+            const int dst = gbase[d] + (lp - tbase[d]);
+            a.keys_out[dst] = k;
+            a.vals_out[dst] = sval[lp];
         }
     }
 }
@@ -561,43 +655,50 @@ template <typename V, int LPR> __global__ __launch_bounds__(256) void bwd_fixup_
     const int sid = blockIdx.x * (256 / FAE_WAVE) + threadIdx.x / FAE_WAVE;
     if (sid >= a.n_spans)
         return;
+    const int lane = fae_lane(), g = lane / LPR, l = lane % LPR;
+    // Two dependent rounds of memory traffic only: (1) the span's border keys together with the
+    // first keys of the next 64 spans, (2) the partial sums together with the weight row.
     const SpanInfo sp = bwd_span_info(a, sid);
+    const int spans_z = a.blk_start[sp.z + 1] - a.blk_start[sp.z];
+    const int j0 = sp.local + 1 + lane;
+    const int follow_key = j0 < spans_z ? a.keys_in[sp.seg0 + j0 * a.span] : KEY_NONE;
     if (!sp.tail_open || (sp.head_open && sp.first_key == sp.last_key))
         return; // nothing crosses the end, or the run began in an earlier span
     const int k = sp.last_key;
     if (k >= a.n_hot[sp.z])
         return;
-    const int lane = fae_lane(), g = lane / LPR, l = lane % LPR;
-    const int spans_z = a.blk_start[sp.z + 1] - a.blk_start[sp.z];
     // following spans that begin with the same key continue the run (keys are sorted)
-    int n_follow = 0;
-    for (int base = sp.local + 1; base < spans_z; base += FAE_WAVE) {
+    uint64_t m = __ballot(follow_key == k);
+    int n_follow = m == ~0ull ? FAE_WAVE : __builtin_ctzll(~m);
+    for (int base = sp.local + 1 + FAE_WAVE; n_follow == base - sp.local - 1 && base < spans_z; base += FAE_WAVE) {
         const int j = base + lane;
         const bool same = j < spans_z && a.keys_in[sp.seg0 + j * a.span] == k;
-        const uint64_t m = __ballot(same);
-        const int run = m == ~0ull ? FAE_WAVE : __builtin_ctzll(~m);
-        n_follow += run;
-        if (run < FAE_WAVE)
-            break;
+        m = __ballot(same);
+        n_follow += m == ~0ull ? FAE_WAVE : __builtin_ctzll(~m);
     }
     const int ncols = a.dim / VW;
     const int first_sid = sid - sp.local;
     for (int c0 = 0; c0 < ncols; c0 += LPR) {
         const int c = c0 + l;
         V acc = bwd_vec<V>::zero();
+        V tail = bwd_vec<V>::zero(), wv = bwd_vec<V>::zero();
+        V *wp = (V *)a.W[sp.z] + (int64_t)k * ncols + c;
         if (c < ncols) {
+            if (g == 0) { // issued together with the heads below
+                tail = ((const V *)(a.partial + ((int64_t)sid * 2 + 1) * a.dim))[c];
+                wv = *wp;
+            }
             for (int j = g; j < n_follow; j += G)
                 bwd_vec<V>::add(acc, ((const V *)(a.partial + (int64_t)(first_sid + sp.local + 1 + j) * 2 * a.dim))[c]);
         }
 #pragma unroll
-        for (int m = LPR; m < FAE_WAVE; m <<= 1) {
-            const V o = bwd_shfl<V>(acc, lane ^ m);
+        for (int mm = LPR; mm < FAE_WAVE; mm <<= 1) {
+            const V o = bwd_shfl<V>(acc, lane ^ mm);
             bwd_vec<V>::add(acc, o);
         }
         if (g == 0 && c < ncols) {
-            bwd_vec<V>::add(acc, ((const V *)(a.partial + ((int64_t)sid * 2 + 1) * a.dim))[c]);
-            V *wp = (V *)a.W[sp.z] + (int64_t)k * ncols + c;
-            *wp = bwd_vec<V>::sgd(*wp, acc, a.lr);
+            bwd_vec<V>::add(acc, tail);
+            *wp = bwd_vec<V>::sgd(wv, acc, a.lr);
         }
     }
 }
@@ -850,7 +951,7 @@ int32_t bwd_sort_stage(fae_ctx *ctx, hipStream_t st, const fae_tables *hot_table
         for (int z = 0; z < nt; ++z) {
             a.blk_start[z] = (int32_t)blocks;
             if (!in_lds[z])
-                blocks += (hot_batch->h_n_lookups[z] + 255) / 256;
+                blocks += (hot_batch->h_n_lookups[z] + KEYS_PER_BLOCK - 1) / KEYS_PER_BLOCK;
         }
         a.blk_start[nt] = (int32_t)blocks;
         a.keys_in = w.keys[0];

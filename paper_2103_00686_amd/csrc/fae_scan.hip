@@ -45,6 +45,40 @@ __global__ __launch_bounds__(256) void fae_fill_kernel(uint32_t *p, int64_t n, u
         p[i] = v;
 }
 
+__global__ __launch_bounds__(256) void fae_copy_probe_kernel(float4 *dst, const float4 *src, int64_t n)
+{
+    // four independent 16-byte loads per lane in flight, then four stores
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    for (; i + 3 * stride < n; i += 4 * stride) {
+        const float4 a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
+        dst[i] = a;
+        dst[i + stride] = b;
+        dst[i + 2 * stride] = c;
+        dst[i + 3 * stride] = d;
+    }
+    for (; i < n; i += stride)
+        dst[i] = src[i];
+}
+
+extern "C" int32_t fae_copy_probe(fae_ctx *ctx, void *dst, const void *src, size_t bytes)
+{
+    if (!ctx || !dst || !src || bytes % 16 != 0 || ((uintptr_t)dst) % 16 != 0 || ((uintptr_t)src) % 16 != 0)
+        return fae_fail(ctx, FAE_EINVAL, "fae_copy_probe: null or misaligned argument");
+    const int64_t n = (int64_t)(bytes / 16);
+    if (n == 0)
+        return FAE_OK;
+    int64_t blocks = (n + 255) / 256;
+    const int64_t cap = (int64_t)ctx->n_cu * 32; // grid-stride: a few waves per SIMD, many vectors per lane
+    if (blocks > cap)
+        blocks = cap;
+    fae_ktimer kt(ctx, FAE_K_COPY_PROBE);
+    hipLaunchKernelGGL(fae_copy_probe_kernel, dim3((unsigned)blocks), dim3(256), 0, ctx->stream, (float4 *)dst,
+                       (const float4 *)src, n);
+    FAE_LAUNCH_CHECK(ctx);
+    return FAE_OK;
+}
+
 int32_t fae_fill_u32(fae_ctx *ctx, void *p, int64_t n_words, uint32_t v)
 {
     if (n_words <= 0)
