@@ -35,6 +35,8 @@ def main():
     ap.add_argument("--steps", type=int, default=1000)
     ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--config", type=int, default=3, help="workload 1..5 (default 3: 26 tables, dim 64, batch 16384)")
+    ap.add_argument("--also", type=str, default="5",
+                    help="comma list of further workloads reported under other_workloads (default 5; '' = none)")
     ap.add_argument("--batches", type=int, default=0, help="distinct hot mini-batches to cycle over (0 = per workload)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--cpu-seconds", type=float, default=10.0)
@@ -45,7 +47,20 @@ def main():
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
         sys.exit(2)
+    line = run_workload(args, args.config, args.steps, args.warmup, with_cpu=not args.no_cpu)
+    others = []
+    for c in [int(x) for x in args.also.split(",") if x.strip()]:
+        if c == args.config:
+            continue
+        # fewer steps for the long-step workloads: keep the whole run within a couple of minutes
+        k = args.steps if c != 5 else max(10, args.steps // 10)
+        o = run_workload(args, c, k, max(3, args.warmup // 5), with_cpu=False)
+        others.append({key: o[key] for key in ("value", "unit", "steps", "ms_per_step", "config", "roofline")})
+    line["other_workloads"] = others
+    print(json.dumps(line), flush=True)
 
+
+def run_workload(args, cfg_id, n_steps, n_warmup, with_cpu):
     import torch
     from paper_2103_00686_amd import binding as B
     from paper_2103_00686_amd import synth as S
@@ -53,9 +68,9 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = torch.device("cuda", 0)
-    w = S.workload(args.config, "full")
+    w = S.workload(cfg_id, "full")
     nt, D = w.n_tables, w.dim
-    n_batches = args.batches or {1: 32, 2: 32, 3: 32, 4: 16, 5: 4}[args.config]
+    n_batches = args.batches or {1: 32, 2: 32, 3: 32, 4: 16, 5: 4}[cfg_id]
     hp = HotPath(w.rows, D, 0)
     for kv in args.set:
         k, v = kv.split("=")
@@ -112,7 +127,7 @@ def main():
             n_part_lookups += sum(ch.n_lookups)
             assert hb.n_samples == w.batch
             batches.append(hb)
-    elif args.config == 1:
+    elif cfg_id == 1:
         for i in range(n_batches):   # each step works on the hot subset of one 1024-sample batch
             ch = S.make_chunk(w, 100 + i, 0, w.batch, device=dev)
             b = B.Batch(w.batch, ch.indices, ch.offsets, ch.n_lookups)
@@ -171,25 +186,25 @@ def main():
 
     # ---- timed region ----------------------------------------------------------------
     nb = len(steps_fn)
-    for i in range(args.warmup):
+    for i in range(n_warmup):
         steps_fn[i % nb]()
     torch.cuda.synchronize()
     hp.sync()
     t0 = time.perf_counter()
-    for i in range(args.steps):
+    for i in range(n_steps):
         steps_fn[i % nb]()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     hp.sync()
-    lookups_done = sum(acct[i % nb]["NL"] for i in range(args.steps))
+    lookups_done = sum(acct[i % nb]["NL"] for i in range(n_steps))
     value = lookups_done / elapsed
-    ms_per_step = elapsed / args.steps * 1e3
-    log(f"{args.steps} steps in {elapsed*1e3:.1f} ms: {ms_per_step*1e3:.1f} us/step, {value/1e9:.3f} G lookups/s")
+    ms_per_step = elapsed / n_steps * 1e3
+    log(f"{n_steps} steps in {elapsed*1e3:.1f} ms: {ms_per_step*1e3:.1f} us/step, {value/1e9:.3f} G lookups/s")
 
     # ---- per-kernel pass (HIP events on the library's stream, same steps) -------------
     B.fae_timing_enable(hp.ctx, True)
     B.fae_timing_reset(hp.ctx)
-    k_steps = min(args.steps, 200)
+    k_steps = min(n_steps, 200)
     for i in range(k_steps):
         steps_fn[i % nb]()
     torch.cuda.synchronize()
@@ -238,20 +253,36 @@ def main():
 
     # ---- the oracle on the host, bounded sample ----------------------------------------
     cpu = None
-    if not args.no_cpu:
+    if with_cpu:
         cpu = cpu_baseline(hp, batches[0], gouts[0], w, args.cpu_seconds)
 
     line = {
         "metric": "hot-embedding lookups/sec (fwd+bwd+SGD)", "value": value, "unit": "lookups/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "n_gpus": 1, "steps": n_steps, "warmup": n_warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": w.name, "config_index": args.config, "tables": nt, "dim": D, "batch": w.batch,
+        "config": {"workload": w.name, "config_index": cfg_id, "tables": nt, "dim": D, "batch": w.batch,
                    "zipf_s": w.zipf_s, "hot_rows": int(sum(hp.n_hot)), "hot_bytes": int(sum(hp.n_hot)) * D * 4,
                    "cutoff_c": c, "lookups_per_step": NL, "distinct_rows_per_step": U, "hot_batches": nb,
                    "profile_samples": w.profile_samples},
         "roofline": roofline, "cpu_baseline": cpu, "stages": {k: float(f"{v:.4g}") for k, v in stages.items()},
     }
-    print(json.dumps(line), flush=True)
+    # measured HBM traffic of the dominant kernel, if a counter summary for it is committed
+    roofline["traffic"] = committed_traffic(cfg_id, dom)
+    del steps_fn, batches, gouts, outs, hp
+    torch.cuda.empty_cache()
+    return line
+
+
+def committed_traffic(cfg_id, kernel):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 --pmc summary (FETCH_SIZE and
+    WRITE_SIZE runs, each scaled by what the same counter reads for the 1 GiB copy probe)."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    try:
+        with open(path) as f:
+            t = json.load(f)
+        return t[f"cfg{cfg_id}"][kernel]["hbm_bytes_per_launch"]
+    except (OSError, KeyError, ValueError):
+        return None
 
 
 def cpu_baseline(hp, hb, gout, w, budget_s):

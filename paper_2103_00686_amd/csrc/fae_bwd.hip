@@ -321,16 +321,7 @@ struct LsortArgs {
     int32_t n_samples;
     int32_t *keys_out, *vals_out;
     uint32_t *status;
-#ifdef FAE_PROBE
-    long long *probe;
-#endif
 };
-
-#ifdef FAE_PROBE
-#define PROBE(i) do { if (blockIdx.x == 0 && threadIdx.x == 0) a.probe[i] = wall_clock64(); } while (0)
-#else
-#define PROBE(i)
-#endif
 
 __global__ __launch_bounds__(LSORT_THREADS) void lds_sort_kernel(LsortArgs a)
 {
@@ -350,7 +341,6 @@ __global__ __launch_bounds__(LSORT_THREADS) void lds_sort_kernel(LsortArgs a)
     // load every key of the table; count the keys of lower parts (they precede this part's output)
     bool bad = false;
     int below = 0;
-    PROBE(0);
     {
         int kk[LSORT_MAX / LSORT_THREADS];
 #pragma unroll
@@ -398,7 +388,6 @@ __global__ __launch_bounds__(LSORT_THREADS) void lds_sort_kernel(LsortArgs a)
         }
     }
     __syncthreads();
-    PROBE(1);
 
     // LSD passes over the bits below part_shift
     const int passes = (pshift + RADIX_BITS - 1) / RADIX_BITS;
@@ -475,7 +464,6 @@ __global__ __launch_bounds__(LSORT_THREADS) void lds_sort_kernel(LsortArgs a)
         __syncthreads();
         cur ^= 1;
     }
-    PROBE(2);
     const int out0 = a.seg_start[z] + n_below;
     const unsigned short *fin = perm[cur];
     bad = false;
@@ -490,7 +478,6 @@ __global__ __launch_bounds__(LSORT_THREADS) void lds_sort_kernel(LsortArgs a)
         a.keys_out[out0 + pos] = keyA[e];
         a.vals_out[out0 + pos] = s;
     }
-    PROBE(3);
     if (bad)
         fae_flag(a.status, FAE_STATUS_ERANGE);
 }
