@@ -41,8 +41,9 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--cpu-seconds", type=float, default=10.0)
     ap.add_argument("--set", action="append", default=[], help="library option name=value (ablation)")
-    ap.add_argument("--presort", action="store_true",
-                    help="start the backward's sort on the side stream before the forward (overlap)")
+    ap.add_argument("--presort", choices=["fused", "side", "none"], default="fused",
+                    help="where the backward's sort runs: in the forward's launch (default, where the shape "
+                         "allows), on the side stream, or inside fae_embbag_bwd_sgd")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -217,6 +218,7 @@ def run_workload(args, cfg_id, n_steps, n_warmup, with_cpu):
     alg = {  # algorithmic bytes per launch
         "fwd": bytes_fwd,
         "bwd_reduce": 8 * NL + 4 * D * NB + 8 * D * U,
+        "fwd_sort": bytes_fwd + 12 * NL,
         "sort_scatter": 16 * NL,
         "sort_hist": 4 * NL,
         "bwd_keys": 12 * NL + off_bytes,

@@ -118,7 +118,8 @@ int32_t fae_set_option(fae_ctx *ctx, const char *name, int64_t value);
 #define FAE_K_BUILD 11       /* classify / scan / gather                        */
 #define FAE_K_OTHER 12
 #define FAE_K_COPY_PROBE 13  /* plain streaming copy (bandwidth ceiling, counter calibration) */
-#define FAE_K_COUNT 14
+#define FAE_K_FWD_SORT 14    /* forward and the backward's LDS sort in one launch */
+#define FAE_K_COUNT 15
 int32_t fae_timing_enable(fae_ctx *ctx, int32_t on);
 int32_t fae_timing_reset(fae_ctx *ctx);
 int32_t fae_timing_read(fae_ctx *ctx, int32_t kernel_class, double *h_total_ms, int64_t *h_launches);
@@ -209,6 +210,15 @@ size_t fae_bwd_workspace_bytes(const fae_tables *hot_tables, int64_t n_samples,
  * workspace must stay untouched in between.  Asynchronous. */
 int32_t fae_embbag_bwd_presort(fae_ctx *ctx, const fae_tables *hot_tables, const fae_batch *hot_batch,
                                void *ws, size_t ws_bytes);
+/* fae_embbag_fwd that also carries the sort of the backward for the same batch: when every
+ * table is one-hot and the batch is small enough for the in-LDS sort (<= 16384 samples),
+ * one launch holds both, the sorting workgroups running beside the row copies; the sorted
+ * pairs stay in ws for the fae_embbag_bwd_sgd call with the same batch and workspace.
+ * For any other shape it is exactly fae_embbag_fwd.  Same results as the separate calls.
+ * Asynchronous. */
+int32_t fae_embbag_fwd_presort(fae_ctx *ctx, const fae_tables *hot_tables, const float *const *h_hotW,
+                               const fae_batch *hot_batch, float *out, int64_t out_row_stride, void *ws,
+                               size_t ws_bytes);
 int32_t fae_embbag_bwd_sgd(fae_ctx *ctx, const fae_tables *hot_tables, float *const *h_hotW,
                            const fae_batch *hot_batch, const float *gout, int64_t gout_row_stride,
                            float lr, const fae_bwd_debug *dbg, void *ws, size_t ws_bytes);

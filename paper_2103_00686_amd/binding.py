@@ -25,6 +25,7 @@ EXPORTS = [
     "fae_profile", "fae_choose_cutoff_workspace_bytes", "fae_choose_cutoff", "fae_count_hot",
     "fae_build_workspace_bytes", "fae_build_hot_tables", "fae_partition_workspace_bytes",
     "fae_partition_batch", "fae_embbag_fwd", "fae_bwd_workspace_bytes", "fae_embbag_bwd_presort",
+    "fae_embbag_fwd_presort",
     "fae_embbag_bwd_sgd",
 ]
 
@@ -183,7 +184,7 @@ def fae_set_option(ctx: Context, name: str, value: int):
     ctx.check(load().fae_set_option(ctx._h, name.encode(), C.c_int64(value)))
 
 
-FAE_K_COUNT = 14
+FAE_K_COUNT = 15
 
 
 def fae_kernel_name(kernel_class: int) -> str:
@@ -308,6 +309,14 @@ def fae_embbag_bwd_presort(ctx: Context, hot_tables: Tables, hot_batch: Batch, w
     t, b = hot_tables.c(), hot_batch.c()
     ctx.check(load().fae_embbag_bwd_presort(ctx._h, C.byref(t), C.byref(b), _ptr(ws, torch.uint8),
                                             C.c_size_t(ws.numel())))
+
+
+def fae_embbag_fwd_presort(ctx: Context, hot_tables: Tables, hotW: List[torch.Tensor], hot_batch: Batch,
+                           out: torch.Tensor, out_row_stride: int, ws: torch.Tensor):
+    t, b = hot_tables.c(), hot_batch.c()
+    ctx.check(load().fae_embbag_fwd_presort(ctx._h, C.byref(t), _ptrs(hotW, torch.float32), C.byref(b),
+                                            _ptr(out, torch.float32), C.c_int64(out_row_stride),
+                                            _ptr(ws, torch.uint8), C.c_size_t(ws.numel())))
 
 
 def fae_embbag_bwd_sgd(ctx: Context, hot_tables: Tables, hotW: List[torch.Tensor], hot_batch: Batch,

@@ -17,6 +17,7 @@
 // Bandwidth bound: per lookup one gradient row is read, per distinct row one weight
 // row is read and written; the sort moves 16 B per lookup and pass.
 #include "fae_internal.h"
+#include "fae_device.h"
 
 // ---------------------------------------------------------------------------------
 // sort geometry
@@ -25,13 +26,10 @@
 #define SORT_ITEMS 16
 #define SORT_WAVES (SORT_THREADS / FAE_WAVE)
 #define SORT_TILE (SORT_THREADS * SORT_ITEMS)
-#define RADIX_BITS 8
-#define RADIX (1 << RADIX_BITS)
 
 #define BWD_SPAN_MAX 256 // sorted lookups per wave in the reduce kernel (multiple of 64)
 #define BWD_SPAN_MIN 64
 #define DBG_TILE 2048
-#define KEY_NONE 0x7fffffff // no carried run / element past the end of the span
 
 struct BwdArgs {
     float *W[FAE_MAX_TABLES];
@@ -305,11 +303,6 @@ __global__ __launch_bounds__(SORT_THREADS) void sort_scatter_kernel(BwdArgs a)
 // the digit, running per-wave offsets).  The parts of a table are disjoint key ranges,
 // so their outputs are laid end to end: part p starts after all keys of parts < p.
 // ---------------------------------------------------------------------------------
-#define LSORT_THREADS 1024
-#define LSORT_WAVES (LSORT_THREADS / FAE_WAVE)
-#define LSORT_MAX 16384
-#define LSORT_MAX_BLOCKS 1024
-
 struct LsortArgs {
     const int32_t *slots[FAE_MAX_TABLES];
     const int32_t *offsets[FAE_MAX_TABLES];
@@ -325,161 +318,10 @@ struct LsortArgs {
 
 __global__ __launch_bounds__(LSORT_THREADS) void lds_sort_kernel(LsortArgs a)
 {
-    __shared__ int keyA[LSORT_MAX];
-    __shared__ unsigned short perm[2][LSORT_MAX];
-    __shared__ int wcnt[LSORT_WAVES][RADIX];
-    __shared__ int scan_lds[LSORT_THREADS / FAE_WAVE + 1];
     const int z = fae_find_table(a.blk_start, a.n_tables, blockIdx.x);
-    const int part = blockIdx.x - a.blk_start[z];
-    const int pshift = a.part_shift[z];
-    const int n = a.seg_start[z + 1] - a.seg_start[z];
-    const int n_hot = a.n_hot[z];
-    const int32_t *off = a.offsets[z];
-    const int w = threadIdx.x / FAE_WAVE, lane = fae_lane();
-    const uint64_t lt_mask = (1ull << lane) - 1ull;
-
-    // load every key of the table; count the keys of lower parts (they precede this part's output)
-    bool bad = false;
-    int below = 0;
-    {
-        int kk[LSORT_MAX / LSORT_THREADS];
-#pragma unroll
-        for (int i = 0; i < LSORT_MAX / LSORT_THREADS; ++i) { // all loads in flight before the first use
-            const int e = threadIdx.x + i * LSORT_THREADS;
-            kk[i] = e < n ? a.slots[z][e] : 0;
-        }
-#pragma unroll
-        for (int i = 0; i < LSORT_MAX / LSORT_THREADS; ++i) {
-            const int e = threadIdx.x + i * LSORT_THREADS;
-            if (e < n) {
-                int k = kk[i];
-                if ((unsigned)k >= (unsigned)n_hot) {
-                    bad = true;
-                    k = n_hot; // behind every valid slot; never dereferenced
-                }
-                keyA[e] = k;
-                below += (k >> pshift) < part ? 1 : 0;
-            }
-        }
-    }
-    if (bad && part == 0)
-        fae_flag(a.status, FAE_STATUS_ERANGE);
-    // ordered selection of this part's lookups: wave w scans positions [w*per, (w+1)*per)
-    const int per = ((n + LSORT_THREADS - 1) / LSORT_THREADS) * FAE_WAVE;
-    __syncthreads();
-    int mine = 0;
-    for (int i = 0; i < per; i += FAE_WAVE) {
-        const int e = w * per + i + lane;
-        mine += (e < n && (keyA[e] >> pshift) == part) ? 1 : 0;
-    }
-    int n_below, n_sel;
-    (void)fae_block_excl_scan<LSORT_THREADS>(below, scan_lds, &n_below);
-    {
-        // per-wave totals -> exclusive prefix over the waves (scan over threads, read at lane 0)
-        const int ex = fae_block_excl_scan<LSORT_THREADS>(mine, scan_lds, &n_sel);
-        int run = __shfl(ex, 0, FAE_WAVE);
-        for (int i = 0; i < per; i += FAE_WAVE) {
-            const int e = w * per + i + lane;
-            const bool sel = e < n && (keyA[e] >> pshift) == part;
-            const uint64_t m = __ballot(sel);
-            if (sel)
-                perm[0][run + __popcll(m & lt_mask)] = (unsigned short)e;
-            run += __popcll(m);
-        }
-    }
-    __syncthreads();
-
-    // LSD passes over the bits below part_shift
-    const int passes = (pshift + RADIX_BITS - 1) / RADIX_BITS;
-    const int digit_bits = passes > 0 ? (pshift + passes - 1) / passes : RADIX_BITS;
-    const int mask = (1 << digit_bits) - 1;
-    const int rounds = (n_sel + LSORT_THREADS - 1) / LSORT_THREADS; // 64-element rounds per wave
-    const int wbase = w * rounds * FAE_WAVE + lane;
-    volatile int *my_cnt = wcnt[w];
-    int cur = 0;
-    for (int pass = 0; pass < passes; ++pass) {
-        const int shift = pass * digit_bits;
-        const unsigned short *src = perm[cur];
-        unsigned short *dst = perm[cur ^ 1];
-#pragma unroll
-        for (int i = 0; i < RADIX / FAE_WAVE; ++i)
-            wcnt[w][i * FAE_WAVE + lane] = 0;
-        __builtin_amdgcn_wave_barrier();
-        // sweep 1: digit histogram of the positions this wave owns
-        // (after the first pass neighbours mostly share a digit: one atomic per run of equal
-        // digits instead of 64 colliding ones)
-        for (int i = 0; i < rounds; ++i) {
-            const int pos = wbase + i * FAE_WAVE;
-            const bool valid = pos < n_sel;
-            const int d = valid ? (keyA[src[pos]] >> shift) & mask : -1;
-            const int dprev = __shfl_up(d, 1, FAE_WAVE);
-            const bool head = valid && (lane == 0 || dprev != d);
-            const uint64_t heads = __ballot(head) | ((__ballot(!valid) & (0 - __ballot(!valid))));
-            if (head) {
-                const uint64_t later = lane == FAE_WAVE - 1 ? 0ull : (heads >> (lane + 1));
-                const int len = later ? __builtin_ctzll(later) + 1 : FAE_WAVE - lane;
-                atomicAdd(&wcnt[w][d], len);
-            }
-        }
-        __syncthreads();
-        // digit t: counts -> exclusive prefix over (digit, wave)
-        int total = 0;
-        if (threadIdx.x < RADIX) {
-            for (int ww = 0; ww < LSORT_WAVES; ++ww) {
-                const int c = wcnt[ww][threadIdx.x];
-                wcnt[ww][threadIdx.x] = total;
-                total += c;
-            }
-        }
-        int all;
-        const int ex = fae_block_excl_scan<LSORT_THREADS>(total, scan_lds, &all);
-        if (threadIdx.x < RADIX) {
-            for (int ww = 0; ww < LSORT_WAVES; ++ww)
-                wcnt[ww][threadIdx.x] += ex;
-        }
-        __syncthreads();
-        // sweep 2: stable ranks, running offsets per wave and digit
-        for (int i = 0; i < rounds; ++i) {
-            const int pos = wbase + i * FAE_WAVE;
-            const bool valid = pos < n_sel;
-            const int e = valid ? src[pos] : 0;
-            const int d = valid ? (keyA[e] >> shift) & mask : 0;
-            uint64_t peers = __ballot(valid);
-#pragma unroll
-            for (int b = 0; b < RADIX_BITS; ++b) {
-                const bool bit = (d >> b) & 1;
-                const uint64_t m = __ballot(bit);
-                peers &= bit ? m : ~m;
-            }
-            const int r = __popcll(peers & lt_mask);
-            const int n_peers = __popcll(peers);
-            if (valid) {
-                const int old = my_cnt[d];
-                if (r == 0)
-                    my_cnt[d] = old + n_peers;
-                dst[old + r] = (unsigned short)e;
-            }
-            __builtin_amdgcn_wave_barrier();
-        }
-        __syncthreads();
-        cur ^= 1;
-    }
-    const int out0 = a.seg_start[z] + n_below;
-    const unsigned short *fin = perm[cur];
-    bad = false;
-    for (int pos = threadIdx.x; pos < n_sel; pos += LSORT_THREADS) {
-        const int e = fin[pos];
-        int s = e;
-        if (off) {
-            s = fae_sample_of(off, a.n_samples, e);
-            if (off[s] > e || off[s + 1] <= e)
-                bad = true; // malformed CSR
-        }
-        a.keys_out[out0 + pos] = keyA[e];
-        a.vals_out[out0 + pos] = s;
-    }
-    if (bad)
-        fae_flag(a.status, FAE_STATUS_ERANGE);
+    lds_sort_block(a.slots[z], a.offsets[z], a.seg_start[z + 1] - a.seg_start[z], a.n_hot[z],
+                   blockIdx.x - a.blk_start[z], a.part_shift[z], a.n_samples, a.keys_out + a.seg_start[z],
+                   a.vals_out + a.seg_start[z], a.status);
 }
 
 // ---------------------------------------------------------------------------------
@@ -906,6 +748,39 @@ int32_t bwd_setup(fae_ctx *ctx, const fae_tables *hot_tables, const fae_batch *h
     return FAE_OK;
 }
 
+// Workgroups per small table for the LDS sort: enough parts to occupy the chip, never lists
+// below ~512 lookups.  part_shift[z]: part of a key = key >> shift; blk_start: prefix of
+// workgroups per table (tables not sorted in LDS get none).  Returns the number of workgroups.
+int lsort_plan(const fae_ctx *ctx, const fae_tables *hot_tables, const fae_batch *hot_batch, const bool *in_lds,
+               int n_lds, int32_t *blk_start, int32_t *part_shift)
+{
+    const int nt = hot_tables->n_tables;
+    int want = 1;
+    while (want < 16 && n_lds * want * 2 <= ctx->n_cu)
+        want <<= 1;
+    int nb = 0;
+    for (int z = 0; z < nt; ++z) {
+        blk_start[z] = nb;
+        if (!in_lds[z])
+            continue;
+        int kbits = 1; // bits of the largest key (n_hot itself marks an invalid slot)
+        while ((hot_tables->h_rows[z] >> kbits) != 0)
+            ++kbits;
+        int parts = want;
+        while (parts > 1 && hot_batch->h_n_lookups[z] / parts < 512)
+            parts >>= 1;
+        int pbits = 0;
+        while ((1 << pbits) < parts)
+            ++pbits;
+        if (pbits > kbits)
+            pbits = kbits;
+        part_shift[z] = kbits - pbits;
+        nb += (int)(hot_tables->h_rows[z] >> part_shift[z]) + 1; // parts that can hold a key: 0 .. (n_hot >> shift)
+    }
+    blk_start[nt] = nb;
+    return nb;
+}
+
 // Steps 1 + 2 on stream `st`: (slot, sample) pairs sorted by slot per table.  *cur_out names
 // the ping-pong buffer that holds the result.
 int32_t bwd_sort_stage(fae_ctx *ctx, hipStream_t st, const fae_tables *hot_tables, const fae_batch *hot_batch,
@@ -987,35 +862,13 @@ int32_t bwd_sort_stage(fae_ctx *ctx, hipStream_t st, const fae_tables *hot_table
     if (n_lds > 0) { // small tables: straight from the slots into the final buffer
         LsortArgs la;
         memset(&la, 0, sizeof(la));
-        // parts per table: enough workgroups to occupy the chip, never lists below ~512 lookups
-        int want = 1;
-        while (want < 16 && n_lds * want * 2 <= ctx->n_cu)
-            want <<= 1;
-        int nb = 0;
         for (int z = 0; z < nt; ++z) {
             la.slots[z] = a.slots[z];
             la.offsets[z] = a.offsets[z];
             la.n_hot[z] = a.n_hot[z];
             la.seg_start[z] = a.seg_start[z];
-            la.blk_start[z] = nb;
-            if (!in_lds[z])
-                continue;
-            int kbits = 1; // bits of the largest key (n_hot itself marks an invalid slot)
-            while ((hot_tables->h_rows[z] >> kbits) != 0)
-                ++kbits;
-            int parts = want;
-            while (parts > 1 && hot_batch->h_n_lookups[z] / parts < 512)
-                parts >>= 1;
-            int pbits = 0;
-            while ((1 << pbits) < parts)
-                ++pbits;
-            if (pbits > kbits)
-                pbits = kbits;
-            la.part_shift[z] = kbits - pbits;
-            // parts that can hold a key: 0 .. (n_hot >> shift)
-            nb += (int)(hot_tables->h_rows[z] >> la.part_shift[z]) + 1;
         }
-        la.blk_start[nt] = nb;
+        const int nb = lsort_plan(ctx, hot_tables, hot_batch, in_lds, n_lds, la.blk_start, la.part_shift);
         la.seg_start[nt] = a.seg_start[nt];
         la.n_tables = nt;
         la.n_samples = a.n_samples;
@@ -1052,11 +905,124 @@ extern "C" int32_t fae_embbag_bwd_presort(fae_ctx *ctx, const fae_tables *hot_ta
         return rc;
     FAE_HIP(ctx, hipEventRecord(ctx->ev_join, ctx->aux_stream));
     ctx->presort.valid = true;
+    ctx->presort.side = true;
     ctx->presort.ws = ws;
     ctx->presort.first_indices = hot_batch->h_indices[0];
     ctx->presort.n_samples = hot_batch->n_samples;
     ctx->presort.n_lookups = su.plan.N;
     ctx->presort.cur = cur;
+    return FAE_OK;
+}
+
+// ---------------------------------------------------------------------------------
+// Forward and the backward's sort in one launch (one-hot tables whose lists fit the LDS
+// sort): the first workgroups sort, the rest copy rows.  The two roles share nothing but
+// the slot lists they both read; the sort is latency/ALU bound on a few CUs while the
+// row copies stream through the others, so the pair takes about as long as the slower one.
+// ---------------------------------------------------------------------------------
+struct FusedArgs {
+    const float *W[FAE_MAX_TABLES];
+    const int32_t *slots[FAE_MAX_TABLES];
+    int32_t n_hot[FAE_MAX_TABLES];
+    int32_t seg_start[FAE_MAX_TABLES + 1];
+    int32_t sort_blk_start[FAE_MAX_TABLES + 1];
+    int32_t part_shift[FAE_MAX_TABLES];
+    int32_t n_tables, dim, n_samples;
+    int32_t n_sort_blocks, fwd_blocks_per_table;
+    int64_t out_stride;
+    float *out;
+    int32_t *keys_out, *vals_out;
+    uint32_t *status;
+    int32_t stream_out;
+};
+
+template <typename V, int LPR> __global__ __launch_bounds__(LSORT_THREADS) void fwd_sort_kernel(FusedArgs a)
+{
+    if ((int)blockIdx.x < a.n_sort_blocks) {
+        const int z = fae_find_table(a.sort_blk_start, a.n_tables, blockIdx.x);
+        lds_sort_block(a.slots[z], nullptr, a.seg_start[z + 1] - a.seg_start[z], a.n_hot[z],
+                       blockIdx.x - a.sort_blk_start[z], a.part_shift[z], a.n_samples, a.keys_out + a.seg_start[z],
+                       a.vals_out + a.seg_start[z], a.status);
+    } else {
+        const int b = blockIdx.x - a.n_sort_blocks;
+        const int z = b / a.fwd_blocks_per_table, bl = b % a.fwd_blocks_per_table;
+        const int64_t s0 = ((int64_t)bl * LSORT_WAVES + threadIdx.x / FAE_WAVE) * FAE_WAVE;
+        fwd_onehot_wave<V, LPR>((const V *)a.W[z], a.slots[z], a.n_hot[z], s0, a.n_samples, a.out + (int64_t)z * a.dim,
+                                a.out_stride, a.dim, a.status, a.stream_out != 0);
+    }
+}
+
+template <int LPR> static void launch_fwd_sort(fae_ctx *ctx, const FusedArgs &a, int blocks)
+{
+    hipLaunchKernelGGL((fwd_sort_kernel<float4, LPR>), dim3(blocks), dim3(LSORT_THREADS), 0, ctx->stream, a);
+}
+
+extern "C" int32_t fae_embbag_fwd_presort(fae_ctx *ctx, const fae_tables *hot_tables, const float *const *h_hotW,
+                                          const fae_batch *hot_batch, float *out, int64_t out_row_stride, void *ws,
+                                          size_t ws_bytes)
+{
+    BwdSetup su;
+    int32_t rc = bwd_setup(ctx, hot_tables, hot_batch, ws, ws_bytes, "fae_embbag_fwd_presort", &su);
+    if (rc != FAE_OK)
+        return rc;
+    const int nt = hot_tables->n_tables, dim = hot_tables->dim;
+    const int64_t S = hot_batch->n_samples;
+    // the fused launch covers the common case of the paper's workloads (every table one-hot,
+    // batch within the LDS sort's reach, 16-byte aligned rows); anything else: plain forward
+    bool fused = !su.empty && ctx->opt_sort != 1 && ctx->opt_fwd == 0 && h_hotW && out && dim % 4 == 0 &&
+                 out_row_stride % 4 == 0 && out_row_stride >= (int64_t)nt * dim && ((uintptr_t)out) % 16 == 0 &&
+                 S <= LSORT_MAX;
+    for (int z = 0; fused && z < nt; ++z)
+        fused = su.a.offsets[z] == nullptr && h_hotW[z] && ((uintptr_t)h_hotW[z]) % 16 == 0;
+    if (!fused)
+        return fae_embbag_fwd(ctx, hot_tables, h_hotW, hot_batch, out, out_row_stride);
+    FAE_HIP(ctx, hipSetDevice(ctx->device));
+    FusedArgs f;
+    memset(&f, 0, sizeof(f));
+    bool in_lds[FAE_MAX_TABLES];
+    for (int z = 0; z < nt; ++z) {
+        f.W[z] = h_hotW[z];
+        f.slots[z] = su.a.slots[z];
+        f.n_hot[z] = su.a.n_hot[z];
+        f.seg_start[z] = su.a.seg_start[z];
+        in_lds[z] = true;
+    }
+    f.seg_start[nt] = su.a.seg_start[nt];
+    f.n_sort_blocks = lsort_plan(ctx, hot_tables, hot_batch, in_lds, nt, f.sort_blk_start, f.part_shift);
+    f.n_tables = nt;
+    f.dim = dim;
+    f.n_samples = (int32_t)S;
+    f.fwd_blocks_per_table = (int32_t)((S + LSORT_THREADS - 1) / LSORT_THREADS);
+    f.out_stride = out_row_stride;
+    f.out = out;
+    f.keys_out = su.w.keys[0];
+    f.vals_out = su.w.vals[0];
+    f.status = ctx->d_block;
+    f.stream_out = ctx->opt_fwd_stream != 0;
+    const int blocks = f.n_sort_blocks + f.fwd_blocks_per_table * nt;
+    int lpr = 1;
+    while (lpr < dim / 4 && lpr < 64)
+        lpr <<= 1;
+    {
+        fae_ktimer kt(ctx, FAE_K_FWD_SORT);
+        switch (lpr) {
+        case 1: launch_fwd_sort<1>(ctx, f, blocks); break;
+        case 2: launch_fwd_sort<2>(ctx, f, blocks); break;
+        case 4: launch_fwd_sort<4>(ctx, f, blocks); break;
+        case 8: launch_fwd_sort<8>(ctx, f, blocks); break;
+        case 16: launch_fwd_sort<16>(ctx, f, blocks); break;
+        case 32: launch_fwd_sort<32>(ctx, f, blocks); break;
+        default: launch_fwd_sort<64>(ctx, f, blocks); break;
+        }
+        FAE_LAUNCH_CHECK(ctx);
+    }
+    ctx->presort.valid = true;
+    ctx->presort.side = false;
+    ctx->presort.ws = ws;
+    ctx->presort.first_indices = hot_batch->h_indices[0];
+    ctx->presort.n_samples = hot_batch->n_samples;
+    ctx->presort.n_lookups = su.plan.N;
+    ctx->presort.cur = 0;
     return FAE_OK;
 }
 
@@ -1103,7 +1069,7 @@ extern "C" int32_t fae_embbag_bwd_sgd(fae_ctx *ctx, const fae_tables *hot_tables
 
     // 1 + 2. sorted (slot, sample) pairs: take them from a matching presort, or sort now
     int cur = 0;
-    if (ctx->presort.valid) {
+    if (ctx->presort.valid && ctx->presort.side) {
         // whatever the side stream was asked to do must be finished before this workspace is used
         FAE_HIP(ctx, hipStreamWaitEvent(ctx->stream, ctx->ev_join, 0));
     }

@@ -194,7 +194,8 @@ extern "C" const char *fae_kernel_name(int32_t k)
 {
     static const char *names[FAE_K_COUNT] = {"fwd",        "bwd_keys",  "sort_hist", "sort_colscan", "sort_scatter",
                                              "bwd_reduce", "bwd_fixup", "lds_sort",  "fill",         "profile",
-                                             "partition",  "build",     "other",     "copy_probe"};
+                                             "partition",  "build",     "other",     "copy_probe",
+                                             "fwd_sort"};
     return (k >= 0 && k < FAE_K_COUNT) ? names[k] : "?";
 }
 

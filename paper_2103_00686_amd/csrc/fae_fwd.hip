@@ -9,6 +9,7 @@
 // Bandwidth bound: per lookup one slot (4 B) and one row (dim*4 B) are read, per bag
 // one row is written.  No arithmetic beyond one add per loaded float.
 #include "fae_internal.h"
+#include "fae_device.h"
 
 struct FwdArgs {
     const float *W[FAE_MAX_TABLES];
@@ -24,28 +25,6 @@ struct FwdArgs {
     float *out;
     uint32_t *status;
     int32_t stream_out; // non-temporal stores for the pooled output
-};
-
-template <typename V> struct vec_ops;
-template <> struct vec_ops<float4> {
-    static __device__ __forceinline__ float4 zero() { return make_float4(0.f, 0.f, 0.f, 0.f); }
-    static __device__ __forceinline__ void add(float4 &a, const float4 &b)
-    {
-        a.x += b.x;
-        a.y += b.y;
-        a.z += b.z;
-        a.w += b.w;
-    }
-    static __device__ __forceinline__ float4 shfl_xor(const float4 &a, int m)
-    {
-        return make_float4(__shfl_xor(a.x, m, FAE_WAVE), __shfl_xor(a.y, m, FAE_WAVE),
-                           __shfl_xor(a.z, m, FAE_WAVE), __shfl_xor(a.w, m, FAE_WAVE));
-    }
-};
-template <> struct vec_ops<float> {
-    static __device__ __forceinline__ float zero() { return 0.f; }
-    static __device__ __forceinline__ void add(float &a, const float &b) { a += b; }
-    static __device__ __forceinline__ float shfl_xor(const float &a, int m) { return __shfl_xor(a, m, FAE_WAVE); }
 };
 
 // one row slice, or zero (and a status flag) when the slot is out of range
@@ -102,68 +81,14 @@ template <typename V, int LPR> __global__ __launch_bounds__(256) void fwd_group_
     }
 }
 
-typedef float fae_v4f __attribute__((ext_vector_type(4)));
-// streaming store: the pooled output is written once and not read again by this kernel
-__device__ __forceinline__ void fwd_store(float4 *p, const float4 &v, bool stream)
-{
-    if (stream)
-        __builtin_nontemporal_store(*(const fae_v4f *)&v, (fae_v4f *)p);
-    else
-        *p = v;
-}
-__device__ __forceinline__ void fwd_store(float *p, const float &v, bool stream)
-{
-    if (stream)
-        __builtin_nontemporal_store(v, p);
-    else
-        *p = v;
-}
-
-// One-hot tables (one lookup per sample): a wave takes 64 consecutive samples, reads their
-// 64 slots with one coalesced load and then copies rows, 64/LPR rows per step, with the
-// loads of up to 16 steps in flight before the first store.
+// One-hot tables: 256 samples per workgroup, 64 per wave.
 template <typename V, int LPR> __global__ __launch_bounds__(256) void fwd_onehot_kernel(FwdArgs a)
 {
-    constexpr int G = FAE_WAVE / LPR;
-    constexpr int STEPS = FAE_WAVE / G;
-    constexpr int UN = STEPS < 16 ? STEPS : 16;
     const int z = fae_find_table(a.blk_start, a.n_tables, blockIdx.x);
     const int bl = blockIdx.x - a.blk_start[z];
-    const int lane = fae_lane(), g = lane / LPR, l = lane % LPR;
     const int64_t s0 = ((int64_t)bl * (256 / FAE_WAVE) + threadIdx.x / FAE_WAVE) * FAE_WAVE;
-    if (s0 >= a.n_samples)
-        return;
-    const int n_hot = a.n_hot[z];
-    int sreg = -1;
-    if (s0 + lane < a.n_samples) {
-        sreg = a.slots[z][s0 + lane];
-        if ((unsigned)sreg >= (unsigned)n_hot) {
-            fae_flag(a.status, FAE_STATUS_ERANGE);
-            sreg = -1; // pooled row of an invalid slot: zeros
-        }
-    }
-    const int ncols = a.dim / (int)(sizeof(V) / sizeof(float));
-    const V *W = (const V *)a.W[z];
-    float *obase = a.out + (int64_t)z * a.dim;
-    for (int c0 = 0; c0 < ncols; c0 += LPR) {
-        const int c = c0 + l;
-        const bool active = c < ncols;
-#pragma unroll
-        for (int i0 = 0; i0 < STEPS; i0 += UN) {
-            V v[UN];
-#pragma unroll
-            for (int u = 0; u < UN; ++u) {
-                const int sl = __shfl(sreg, (i0 + u) * G + g, FAE_WAVE);
-                v[u] = (active && sl >= 0) ? W[(int64_t)sl * ncols + c] : vec_ops<V>::zero();
-            }
-#pragma unroll
-            for (int u = 0; u < UN; ++u) {
-                const int64_t s = s0 + (i0 + u) * G + g;
-                if (active && s < a.n_samples)
-                    fwd_store((V *)(obase + s * a.out_stride) + c, v[u], a.stream_out != 0);
-            }
-        }
-    }
+    fwd_onehot_wave<V, LPR>((const V *)a.W[z], a.slots[z], a.n_hot[z], s0, a.n_samples, a.out + (int64_t)z * a.dim,
+                            a.out_stride, a.dim, a.status, a.stream_out != 0);
 }
 
 template <typename V, int LPR> __global__ __launch_bounds__(256) void fwd_wave_kernel(FwdArgs a)

@@ -42,6 +42,7 @@ struct fae_ctx {
     hipEvent_t ev_fork = nullptr, ev_join = nullptr;
     struct {
         bool valid = false;
+        bool side = false; // sorted on the side stream (needs the join event) or on the main stream
         const void *ws = nullptr;
         const void *first_indices = nullptr;
         int64_t n_samples = 0, n_lookups = 0;

@@ -72,11 +72,11 @@ class HotPath:
             t = self._hot_tables = B.Tables(list(self.n_hot), self.dim)
         return t
 
-    def prepare_step(self, hb: HotBatch, gout: torch.Tensor, out: torch.Tensor, lr: float, presort: bool = True):
+    def prepare_step(self, hb: HotBatch, gout: torch.Tensor, out: torch.Tensor, lr: float, presort: str = "fused"):
         """Pre-marshalled forward + backward/SGD on one hot batch: returns a zero-argument
-        callable that only issues the library calls (for tight training loops).  With
-        ``presort`` the backward's sort is started on the side stream first, so it overlaps
-        the forward."""
+        callable that only issues the library calls (for tight training loops).  presort:
+        "fused" = forward and the backward's sort in one launch where the shape allows,
+        "side" = the sort on the side stream before the forward, "none" = separate calls."""
         import ctypes as C
         lib = B.load()
         t, b = self.hot_tables.c(), hb.batch().c()
@@ -89,9 +89,12 @@ class HotPath:
         keep = (t, b, wptr, ws, out, gout, hb)
 
         def step():
-            rc = lib.fae_embbag_bwd_presort(h, tr, br, a_ws, n_ws) if presort else 0
-            if rc == 0:
-                rc = lib.fae_embbag_fwd(h, tr, wptr, br, a_out, stride)
+            if presort == "fused":
+                rc = lib.fae_embbag_fwd_presort(h, tr, wptr, br, a_out, stride, a_ws, n_ws)
+            else:
+                rc = lib.fae_embbag_bwd_presort(h, tr, br, a_ws, n_ws) if presort == "side" else 0
+                if rc == 0:
+                    rc = lib.fae_embbag_fwd(h, tr, wptr, br, a_out, stride)
             if rc == 0:
                 rc = lib.fae_embbag_bwd_sgd(h, tr, wptr, br, a_gout, stride, c_lr, None, a_ws, n_ws)
             if rc != 0:
@@ -162,6 +165,13 @@ class HotPath:
 
     def presort(self, hb: HotBatch):
         B.fae_embbag_bwd_presort(self.ctx, self.hot_tables, hb.batch(), self.bwd_workspace(hb))
+
+    def forward_presort(self, hb: HotBatch, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+        if out is None:
+            out = torch.empty((hb.n_samples, self.nt, self.dim), dtype=torch.float32, device=self.dev)
+        B.fae_embbag_fwd_presort(self.ctx, self.hot_tables, self.hotW, hb.batch(), out, self.nt * self.dim,
+                                 self.bwd_workspace(hb))
+        return out
 
     def backward_sgd(self, hb: HotBatch, gout: torch.Tensor, lr: float, debug: bool = False):
         ws = self.bwd_workspace(hb)

@@ -136,10 +136,11 @@ class Pipeline:
         return hb
 
     # a6
-    def check_forward(self, hb: HotBatch, exact_gather: bool = True):
+    def check_forward(self, hb: HotBatch, exact_gather: bool = True, fused: bool = False):
         """exact_gather: single-row bags must be bit-identical copies (only while the two
-        sides hold bit-identical weights, i.e. before the first update)."""
-        out = self.hp.forward(hb).cpu().numpy()
+        sides hold bit-identical weights, i.e. before the first update).  fused: through
+        fae_embbag_fwd_presort (forward and the backward's sort in one launch)."""
+        out = (self.hp.forward_presort(hb) if fused else self.hp.forward(hb)).cpu().numpy()
         slots = [s.cpu().numpy() for s in hb.slots]
         offs = [None if o is None else o.cpu().numpy() for o in hb.offsets]
         ref, mag = O.embbag_fwd(self.hotW, hb.n_samples, slots, offs, want_mag=True)

@@ -39,6 +39,10 @@ def test_workload_end_to_end(dev, cfg_id, materialise):
     p.check_forward(batches[-1], exact_gather=False)           # sees the updated rows
     p.check_backward(batches[-1], stream=21, presort=batches[-1])   # in-place state carried over; sort on the side stream
     p.check_backward(batches[0], stream=22, presort=batches[-1])    # a presort of another batch is not used
+    p.check_forward(batches[0], exact_gather=False, fused=True)     # forward + sort in one launch ...
+    p.check_backward(batches[0], stream=23)                         # ... consumed by this backward
+    p.check_forward(batches[0], exact_gather=False, fused=True)
+    p.check_backward(batches[-1], stream=24)                        # sorted pairs of another batch: not used
 
 
 @pytest.mark.parametrize("variant", [1, 2])
