@@ -632,7 +632,7 @@ BwdPlan bwd_plan(int nt, const int64_t *h_n_lookups)
 int bwd_span(const BwdPlan &p, int n_cu)
 {
     int span = BWD_SPAN_MAX;
-    while (span > BWD_SPAN_MIN && p.N / span < 16LL * n_cu)
+    while (span > BWD_SPAN_MIN && p.N / span < 8LL * n_cu)
         span >>= 1;
     return span;
 }
@@ -1053,7 +1053,7 @@ extern "C" int32_t fae_embbag_bwd_sgd(fae_ctx *ctx, const fae_tables *hot_tables
     const BwdPlan &plan = su.plan;
     const BwdWs &w = su.w;
     BwdArgs &a = su.a;
-    const int span = bwd_span(plan, ctx->n_cu);
+    const int span = ctx->opt_span ? (int)ctx->opt_span : bwd_span(plan, ctx->n_cu);
     bool vec = (dim % 4 == 0) && (gout_row_stride % 4 == 0) && (((uintptr_t)gout) % 16 == 0);
     for (int z = 0; z < nt; ++z) {
         if (!h_hotW[z] && hot_tables->h_rows[z] > 0)

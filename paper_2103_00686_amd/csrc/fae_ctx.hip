@@ -215,6 +215,8 @@ extern "C" int32_t fae_set_option(fae_ctx *ctx, const char *name, int64_t value)
         ctx->opt_sort = value;
     else if (!strcmp(name, "fwd_stream_out") && value >= 0 && value <= 1)
         ctx->opt_fwd_stream = value;
+    else if (!strcmp(name, "reduce_span") && (value == 0 || value == 64 || value == 128 || value == 256))
+        ctx->opt_span = value;
     else
         return fae_fail(ctx, FAE_EINVAL, "fae_set_option: unknown option or value: %s=%lld", name,
                         (long long)value);

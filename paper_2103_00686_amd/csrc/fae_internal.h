@@ -36,6 +36,7 @@ struct fae_ctx {
     int64_t opt_fwd = 0;     // 0 auto, 1 group-per-bag, 2 wave-per-bag
     int64_t opt_sort = 0;    // 0 auto, 1 global radix, 2 LDS per table
     int64_t opt_fwd_stream = 1; // non-temporal stores for the pooled output
+    int64_t opt_span = 0;       // lookups per wave in the reduce kernel (0 = auto)
     char err[512] = {0};
     // side stream for work that may overlap the main stream (backward presort)
     hipStream_t aux_stream = nullptr;
