@@ -110,6 +110,91 @@ __device__ __forceinline__ void fwd_onehot_wave(const V *W, const int32_t *slots
 #define LSORT_MAX 16384
 #define LSORT_MAX_BLOCKS 1024
 
+// LSD radix passes inside LDS on a 16-bit permutation: perm0[0..n_sel) holds indices into
+// `keys`; sorts them stably by the low `nbits` bits of (keys[idx] - sub), ping-ponging between
+// perm0 and perm1.  Returns 0 / 1: which of the two holds the result.  A pass makes two sweeps:
+// a per-wave digit histogram (one LDS atomic per run of equal digits), then a stable ranking
+// (wave-level match on the digit, running per-wave offsets).  All LSORT_THREADS threads call it.
+__device__ __forceinline__ int lds_radix_passes(const int *keys, int sub, int n_sel, int nbits, unsigned short *perm0,
+                                                unsigned short *perm1, int (*wcnt)[RADIX], int *scan_lds)
+{
+    const int w = threadIdx.x / FAE_WAVE, lane = fae_lane();
+    const uint64_t lt_mask = (1ull << lane) - 1ull;
+    const int passes = (nbits + RADIX_BITS - 1) / RADIX_BITS;
+    const int digit_bits = passes > 0 ? (nbits + passes - 1) / passes : RADIX_BITS;
+    const int mask = (1 << digit_bits) - 1;
+    const int rounds = (n_sel + LSORT_THREADS - 1) / LSORT_THREADS; // 64-element rounds per wave
+    const int wbase = w * rounds * FAE_WAVE + lane;
+    volatile int *my_cnt = wcnt[w];
+    int cur = 0;
+    for (int pass = 0; pass < passes; ++pass) {
+        const int shift = pass * digit_bits;
+        const unsigned short *src = cur ? perm1 : perm0;
+        unsigned short *dst = cur ? perm0 : perm1;
+#pragma unroll
+        for (int i = 0; i < RADIX / FAE_WAVE; ++i)
+            wcnt[w][i * FAE_WAVE + lane] = 0;
+        __builtin_amdgcn_wave_barrier();
+        // sweep 1: digit histogram of the positions this wave owns
+        for (int i = 0; i < rounds; ++i) {
+            const int pos = wbase + i * FAE_WAVE;
+            const bool valid = pos < n_sel;
+            const int d = valid ? ((keys[src[pos]] - sub) >> shift) & mask : -1;
+            const int dprev = __shfl_up(d, 1, FAE_WAVE);
+            const bool head = valid && (lane == 0 || dprev != d);
+            const uint64_t heads = __ballot(head) | ((__ballot(!valid) & (0 - __ballot(!valid))));
+            if (head) {
+                const uint64_t later = lane == FAE_WAVE - 1 ? 0ull : (heads >> (lane + 1));
+                const int len = later ? __builtin_ctzll(later) + 1 : FAE_WAVE - lane;
+                atomicAdd(&wcnt[w][d], len);
+            }
+        }
+        __syncthreads();
+        // digit t: counts -> exclusive prefix over (digit, wave)
+        int total = 0;
+        if (threadIdx.x < RADIX) {
+            for (int ww = 0; ww < LSORT_WAVES; ++ww) {
+                const int c = wcnt[ww][threadIdx.x];
+                wcnt[ww][threadIdx.x] = total;
+                total += c;
+            }
+        }
+        int all;
+        const int ex = fae_block_excl_scan<LSORT_THREADS>(total, scan_lds, &all);
+        if (threadIdx.x < RADIX) {
+            for (int ww = 0; ww < LSORT_WAVES; ++ww)
+                wcnt[ww][threadIdx.x] += ex;
+        }
+        __syncthreads();
+        // sweep 2: stable ranks, running offsets per wave and digit
+        for (int i = 0; i < rounds; ++i) {
+            const int pos = wbase + i * FAE_WAVE;
+            const bool valid = pos < n_sel;
+            const int e = valid ? src[pos] : 0;
+            const int d = valid ? ((keys[e] - sub) >> shift) & mask : 0;
+            uint64_t peers = __ballot(valid);
+#pragma unroll
+            for (int b = 0; b < RADIX_BITS; ++b) {
+                const bool bit = (d >> b) & 1;
+                const uint64_t m = __ballot(bit);
+                peers &= bit ? m : ~m;
+            }
+            const int r = __popcll(peers & lt_mask);
+            const int n_peers = __popcll(peers);
+            if (valid) {
+                const int old = my_cnt[d];
+                if (r == 0)
+                    my_cnt[d] = old + n_peers;
+                dst[old + r] = (unsigned short)e;
+            }
+            __builtin_amdgcn_wave_barrier();
+        }
+        __syncthreads();
+        cur ^= 1;
+    }
+    return cur;
+}
+
 __device__ __forceinline__ void lds_sort_block(const int32_t *slots, const int32_t *off, int n, int n_hot, int part,
                                                int pshift, int n_samples, int32_t *keys_out, int32_t *vals_out,
                                                uint32_t *status)
@@ -173,80 +258,7 @@ __device__ __forceinline__ void lds_sort_block(const int32_t *slots, const int32
     __syncthreads();
 
     // LSD passes over the bits below part_shift
-    const int passes = (pshift + RADIX_BITS - 1) / RADIX_BITS;
-    const int digit_bits = passes > 0 ? (pshift + passes - 1) / passes : RADIX_BITS;
-    const int mask = (1 << digit_bits) - 1;
-    const int rounds = (n_sel + LSORT_THREADS - 1) / LSORT_THREADS; // 64-element rounds per wave
-    const int wbase = w * rounds * FAE_WAVE + lane;
-    volatile int *my_cnt = wcnt[w];
-    int cur = 0;
-    for (int pass = 0; pass < passes; ++pass) {
-        const int shift = pass * digit_bits;
-        const unsigned short *src = perm[cur];
-        unsigned short *dst = perm[cur ^ 1];
-#pragma unroll
-        for (int i = 0; i < RADIX / FAE_WAVE; ++i)
-            wcnt[w][i * FAE_WAVE + lane] = 0;
-        __builtin_amdgcn_wave_barrier();
-        // sweep 1: digit histogram of the positions this wave owns
-        // (after the first pass neighbours mostly share a digit: one atomic per run of equal
-        // digits instead of 64 colliding ones)
-        for (int i = 0; i < rounds; ++i) {
-            const int pos = wbase + i * FAE_WAVE;
-            const bool valid = pos < n_sel;
-            const int d = valid ? (keyA[src[pos]] >> shift) & mask : -1;
-            const int dprev = __shfl_up(d, 1, FAE_WAVE);
-            const bool head = valid && (lane == 0 || dprev != d);
-            const uint64_t heads = __ballot(head) | ((__ballot(!valid) & (0 - __ballot(!valid))));
-            if (head) {
-                const uint64_t later = lane == FAE_WAVE - 1 ? 0ull : (heads >> (lane + 1));
-                const int len = later ? __builtin_ctzll(later) + 1 : FAE_WAVE - lane;
-                atomicAdd(&wcnt[w][d], len);
-            }
-        }
-        __syncthreads();
-        // digit t: counts -> exclusive prefix over (digit, wave)
-        int total = 0;
-        if (threadIdx.x < RADIX) {
-            for (int ww = 0; ww < LSORT_WAVES; ++ww) {
-                const int c = wcnt[ww][threadIdx.x];
-                wcnt[ww][threadIdx.x] = total;
-                total += c;
-            }
-        }
-        int all;
-        const int ex = fae_block_excl_scan<LSORT_THREADS>(total, scan_lds, &all);
-        if (threadIdx.x < RADIX) {
-            for (int ww = 0; ww < LSORT_WAVES; ++ww)
-                wcnt[ww][threadIdx.x] += ex;
-        }
-        __syncthreads();
-        // sweep 2: stable ranks, running offsets per wave and digit
-        for (int i = 0; i < rounds; ++i) {
-            const int pos = wbase + i * FAE_WAVE;
-            const bool valid = pos < n_sel;
-            const int e = valid ? src[pos] : 0;
-            const int d = valid ? (keyA[e] >> shift) & mask : 0;
-            uint64_t peers = __ballot(valid);
-#pragma unroll
-            for (int b = 0; b < RADIX_BITS; ++b) {
-                const bool bit = (d >> b) & 1;
-                const uint64_t m = __ballot(bit);
-                peers &= bit ? m : ~m;
-            }
-            const int r = __popcll(peers & lt_mask);
-            const int n_peers = __popcll(peers);
-            if (valid) {
-                const int old = my_cnt[d];
-                if (r == 0)
-                    my_cnt[d] = old + n_peers;
-                dst[old + r] = (unsigned short)e;
-            }
-            __builtin_amdgcn_wave_barrier();
-        }
-        __syncthreads();
-        cur ^= 1;
-    }
+    const int cur = lds_radix_passes(keyA, 0, n_sel, pshift, perm[0], perm[1], wcnt, scan_lds);
     const int out0 = n_below;
     const unsigned short *fin = perm[cur];
     bad = false;

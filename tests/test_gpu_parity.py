@@ -97,11 +97,14 @@ def test_forward_backward_shapes(dev, variant, dim):
         assert got[mask].tobytes() == before[z][mask].tobytes()
 
 
-def test_backward_long_runs_and_many_tiles(dev):
-    """One slot repeated tens of thousands of times (several pieces of a long run), runs just
-    below/above the long-run limit, more than one sort tile, three radix passes."""
+@pytest.mark.parametrize("S_,sort_variant", [(50_000, 0), (50_000, 1), (300_000, 0)])
+def test_backward_long_runs_and_many_tiles(dev, S_, sort_variant):
+    """One slot repeated tens of thousands of times (a run that crosses hundreds of spans and, in
+    the key-range sort, a single value larger than the LDS buffers), runs of about two spans,
+    several sort tiles, three radix passes.  50 000 lookups take the key-range sort (or the
+    global passes when forced), 300 000 the global passes."""
     rng = np.random.default_rng(7)
-    dim, n_hot, S_ = 64, 5_000_000, 50_000
+    dim, n_hot = 64, 5_000_000
     slots = rng.integers(0, n_hot, S_).astype(np.int32)
     slots[:20_000] = 4_999_999
     slots[20_000:20_129] = 17          # 129 > limit
@@ -111,6 +114,7 @@ def test_backward_long_runs_and_many_tiles(dev):
     lr = 0.01
     rows = np.unique(slots)
     hp = HotPath([n_hot], dim, 0)
+    B.fae_set_option(hp.ctx, "sort_variant", sort_variant)
     hp.n_hot = [n_hot]
     hp.hotW = [torch.zeros((n_hot, dim), dtype=torch.float32, device=dev)]
     w_rows = (rng.random((rows.size, dim), dtype=np.float32) - 0.5)
