@@ -97,7 +97,8 @@ const char *fae_version(void);
 int32_t fae_sync(fae_ctx *ctx);
 /* Tuning/ablation switches, e.g. ("profile_variant", 0=auto 1=global atomics
  * 2=LDS-privatised), ("fwd_variant", 0=auto 1=group-per-bag 2=wave-per-bag),
- * ("sort_variant", 0=auto 1=global radix 2=LDS per table). */
+ * ("sort_variant", 0=auto, 1=global radix with three kernels per pass, 2=LDS per table
+ * where it fits, 3=global radix with one kernel per pass). */
 int32_t fae_set_option(fae_ctx *ctx, const char *name, int64_t value);
 
 /* ---- per-kernel timing (measurement aid; off by default) ---------------------- */

@@ -211,7 +211,7 @@ extern "C" int32_t fae_set_option(fae_ctx *ctx, const char *name, int64_t value)
         ctx->opt_profile = value;
     else if (!strcmp(name, "fwd_variant") && value >= 0 && value <= 2)
         ctx->opt_fwd = value;
-    else if (!strcmp(name, "sort_variant") && value >= 0 && value <= 2)
+    else if (!strcmp(name, "sort_variant") && value >= 0 && value <= 3)
         ctx->opt_sort = value;
     else if (!strcmp(name, "fwd_stream_out") && value >= 0 && value <= 1)
         ctx->opt_fwd_stream = value;
@@ -244,6 +244,8 @@ int32_t fae_sync_status(fae_ctx *ctx)
     hipLaunchKernelGGL(fae_clear_words_kernel, dim3(1), dim3(64), 0, ctx->stream, ctx->d_block, 1);
     FAE_LAUNCH_CHECK(ctx);
     FAE_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    if (st & FAE_STATUS_EINTERNAL)
+        return fae_fail(ctx, FAE_EHIP, "internal: a bounded wait inside a kernel gave up; results of that call are invalid");
     if (st & FAE_STATUS_ERANGE)
         return fae_fail(ctx, FAE_ERANGE, "device detected an index/slot out of range or a malformed CSR");
     return fae_fail(ctx, FAE_ENOSPC, "device detected an output capacity overflow");

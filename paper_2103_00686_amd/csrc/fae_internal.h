@@ -15,6 +15,7 @@
 // ---------------------------------------------------------------------------------
 #define FAE_STATUS_ERANGE 1u
 #define FAE_STATUS_ENOSPC 2u
+#define FAE_STATUS_EINTERNAL 4u // a bounded wait inside a kernel gave up
 
 // word offsets inside the 4 KiB device / pinned-host blocks
 #define FAE_BLK_STATUS 0
@@ -79,6 +80,7 @@ int32_t fae_check_batch(fae_ctx *ctx, const fae_tables *t, const fae_batch *b, c
 int32_t fae_scan_i32(fae_ctx *ctx, int32_t *data, int64_t n);
 // fill n 32-bit words (a kernel, not a memset node: stays graph-capturable)
 int32_t fae_fill_u32(fae_ctx *ctx, void *p, int64_t n_words, uint32_t v);
+int32_t fae_fill_u32_on(fae_ctx *ctx, hipStream_t st, void *p, int64_t n_words, uint32_t v);
 
 #define FAE_HIP(ctx, call)                                                                   \
     do {                                                                                     \

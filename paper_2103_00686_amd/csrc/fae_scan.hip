@@ -81,13 +81,18 @@ extern "C" int32_t fae_copy_probe(fae_ctx *ctx, void *dst, const void *src, size
 
 int32_t fae_fill_u32(fae_ctx *ctx, void *p, int64_t n_words, uint32_t v)
 {
+    return fae_fill_u32_on(ctx, ctx->stream, p, n_words, v);
+}
+
+int32_t fae_fill_u32_on(fae_ctx *ctx, hipStream_t st, void *p, int64_t n_words, uint32_t v)
+{
     if (n_words <= 0)
         return FAE_OK;
     int64_t blocks = (n_words + 255) / 256;
     if (blocks > 65536)
         blocks = 65536;
-    fae_ktimer kt(ctx, FAE_K_FILL);
-    hipLaunchKernelGGL(fae_fill_kernel, dim3((unsigned)blocks), dim3(256), 0, ctx->stream, (uint32_t *)p, n_words, v);
+    fae_ktimer kt(ctx, FAE_K_FILL, st);
+    hipLaunchKernelGGL(fae_fill_kernel, dim3((unsigned)blocks), dim3(256), 0, st, (uint32_t *)p, n_words, v);
     FAE_LAUNCH_CHECK(ctx);
     return FAE_OK;
 }

@@ -97,12 +97,13 @@ def test_forward_backward_shapes(dev, variant, dim):
         assert got[mask].tobytes() == before[z][mask].tobytes()
 
 
-@pytest.mark.parametrize("S_,sort_variant", [(50_000, 0), (50_000, 1), (300_000, 0)])
+@pytest.mark.parametrize("S_,sort_variant", [(50_000, 0), (50_000, 1), (50_000, 3), (300_000, 0), (300_000, 1)])
 def test_backward_long_runs_and_many_tiles(dev, S_, sort_variant):
     """One slot repeated tens of thousands of times (a run that crosses hundreds of spans and, in
     the key-range sort, a single value larger than the LDS buffers), runs of about two spans,
     several sort tiles, three radix passes.  50 000 lookups take the key-range sort (or the
-    global passes when forced), 300 000 the global passes."""
+    global passes when forced: 1 = three kernels per pass, 3 = one chained kernel per pass),
+    300 000 the global passes (chained by default at this size)."""
     rng = np.random.default_rng(7)
     dim, n_hot = 64, 5_000_000
     slots = rng.integers(0, n_hot, S_).astype(np.int32)
