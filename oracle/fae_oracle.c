@@ -70,6 +70,51 @@ int64_t orc_count_hot(const uint32_t *cnt, int64_t n_rows, uint32_t H)
     return n;
 }
 
+/* ------------------------------------------------------------------ */
+/* Estimating the hot size from sampled chunks of the logger           */
+/* (Sec. 4.1.2, "Estimating the hot embedding table sizes per          */
+/* threshold" and "Confidence in the estimated embedding table size"). */
+/* The chunk numbers are inputs: the caller draws them, without        */
+/* replacement, from the N = ceil(n_rows / m) aligned chunks of m      */
+/* consecutive logger entries.                                         */
+/* ------------------------------------------------------------------ */
+
+/* Eq. 2: C_i = number of entries of chunk i with k >= H.  The last chunk of a
+ * table may hold fewer than m entries; the missing ones count as not hot. */
+int64_t orc_chunk_count(const uint32_t *cnt, int64_t n_rows, int64_t m,
+                        int64_t chunk, uint32_t H)
+{
+    int64_t C = 0;
+    for (int64_t j = 0; j < m; ++j) {
+        int64_t r = chunk * m + j;
+        if (r < n_rows && cnt[r] >= H)
+            C += 1;
+    }
+    return C;
+}
+
+/* Eq. 3: mean of the n chunk counts, and their standard deviation s (the
+ * sample standard deviation, divisor n - 1, as the t-interval takes it). */
+void orc_mean_std(const int64_t *Ci, int64_t n, double *ybar, double *s)
+{
+    double sum = 0.0;
+    for (int64_t i = 0; i < n; ++i)
+        sum += (double)Ci[i];
+    *ybar = sum / (double)n;
+    double ss = 0.0;
+    for (int64_t i = 0; i < n; ++i)
+        ss += ((double)Ci[i] - *ybar) * ((double)Ci[i] - *ybar);
+    *s = n > 1 ? sqrt(ss / (double)(n - 1)) : 0.0;
+}
+
+/* Eq. 4: half-width of the confidence interval of the mean,
+ * t_{alpha/2} * sqrt(((N - n) / N) * (s^2 / n)); the caller supplies the
+ * quantile t_{alpha/2} of Student's t with n - 1 degrees of freedom. */
+double orc_ci_halfwidth(double s, int64_t n, int64_t N, double t_quantile)
+{
+    return t_quantile * sqrt(((double)(N - n) / (double)N) * (s * s / (double)n));
+}
+
 /* ceil(c * T / n) in exact integer arithmetic (c*T < 2^63 is a precondition). */
 static uint32_t scaled_cutoff(int64_t c, int64_t T, int64_t n)
 {
@@ -149,6 +194,18 @@ void orc_gather_rows(const float *W, int32_t dim, const int32_t *hot_ids,
     for (int64_t s = 0; s < n_hot; ++s)
         for (int32_t c = 0; c < dim; ++c)
             hotW[s * dim + c] = W[(int64_t)hot_ids[s] * dim + c];
+}
+
+/* Embedding synchronisation when training switches from hot to cold mini-batches
+ * (Sec. 3 (4); Sec. 6.2, "Embedding Synchronization"): the updated hot rows go back to
+ * their places in the full table; every other row of the full table stays as it is.
+ * The opposite direction is orc_gather_rows. */
+void orc_scatter_rows(float *W, int32_t dim, const int32_t *hot_ids,
+                      int64_t n_hot, const float *hotW)
+{
+    for (int64_t s = 0; s < n_hot; ++s)
+        for (int32_t c = 0; c < dim; ++c)
+            W[(int64_t)hot_ids[s] * dim + c] = hotW[s * dim + c];
 }
 
 /* Procedural initial weights of a virtual table (counter-based; the synthetic

@@ -42,6 +42,8 @@ def lib():
         _lib.orc_cutoff_int.restype = C.c_uint32
         _lib.orc_cutoff_int.argtypes = [C.c_double]
         _lib.orc_count_hot.restype = C.c_int64
+        _lib.orc_chunk_count.restype = C.c_int64
+        _lib.orc_ci_halfwidth.restype = C.c_double
         _lib.orc_classify.restype = C.c_int64
         _lib.orc_runs.restype = C.c_int64
         _lib.orc_w0.restype = C.c_float
@@ -129,6 +131,74 @@ def gather_rows(W: np.ndarray, hot_ids: np.ndarray) -> np.ndarray:
     hot_ids = _arr(hot_ids, np.int32)
     out = np.empty((hot_ids.size, W.shape[1]), dtype=np.float32)
     lib().orc_gather_rows(_p(W), C.c_int32(W.shape[1]), _p(hot_ids), C.c_int64(hot_ids.size), _p(out))
+    return out
+
+
+def scatter_rows(W: np.ndarray, hot_ids: np.ndarray, hotW: np.ndarray) -> np.ndarray:
+    """Full table with the hot rows written back (a copy; Sec. 3 (4), Sec. 6.2)."""
+    W = _arr(W, np.float32).copy()
+    hot_ids = _arr(hot_ids, np.int32)
+    hotW = _arr(hotW, np.float32)
+    assert hotW.shape == (hot_ids.size, W.shape[1])
+    lib().orc_scatter_rows(_p(W), C.c_int32(W.shape[1]), _p(hot_ids), C.c_int64(hot_ids.size), _p(hotW))
+    return W
+
+
+def chunk_counts(cnt: np.ndarray, m: int, chunks: np.ndarray, H: int) -> np.ndarray:
+    """Eq. 2 for every sampled chunk of one table's logger."""
+    cnt = _arr(cnt, np.uint32)
+    out = np.empty(len(chunks), dtype=np.int64)
+    for i, ch in enumerate(chunks):
+        out[i] = lib().orc_chunk_count(_p(cnt), C.c_int64(cnt.size), C.c_int64(m), C.c_int64(int(ch)), C.c_uint32(H))
+    return out
+
+
+def mean_std(Ci: np.ndarray):
+    """Eq. 3: (mean, sample standard deviation) of the chunk counts."""
+    Ci = _arr(Ci, np.int64)
+    y, s = C.c_double(0), C.c_double(0)
+    lib().orc_mean_std(_p(Ci), C.c_int64(Ci.size), C.byref(y), C.byref(s))
+    return y.value, s.value
+
+
+def t_quantile(confidence: float, n: int) -> float:
+    """t_{alpha/2} of Student's t with n - 1 degrees of freedom (library routine)."""
+    from scipy import stats
+    return float(stats.t.ppf(1.0 - (1.0 - confidence) / 2.0, n - 1))
+
+
+def estimate_hot_rows(cnt: np.ndarray, m: int, chunks: np.ndarray, H: int, confidence: float):
+    """Sec. 4.1.2: estimated number of hot rows of one table from n sampled chunks and
+    its confidence interval.  Per-chunk mean and half-width (Eq. 3, Eq. 4) are scaled by
+    the number of chunks N.  Returns (estimate, half_width, ybar, s)."""
+    cnt = _arr(cnt, np.uint32)
+    n = len(chunks)
+    N = -(-cnt.size // m)
+    ybar, s = mean_std(chunk_counts(cnt, m, chunks, H))
+    hw = lib().orc_ci_halfwidth(C.c_double(s), C.c_int64(n), C.c_int64(N), C.c_double(t_quantile(confidence, n)))
+    return ybar * N, hw * N, ybar, s
+
+
+def shuffle_scheduler(losses: Sequence[float], r0: float = 50.0, u: int = 4) -> List[float]:
+    """Shuffle Scheduler (Sec. 5, Eq. 5): the rate after each swap, given the test loss
+    measured after each swap.  Rates are the p of R(p), kept inside [1, 100].
+      - loss not below the previous swap's loss      -> rate halves (not below R(1));
+      - loss fell at each of the last u swaps        -> rate doubles (not above R(100)),
+        and the count of successive falls starts again;
+      - otherwise the rate stays.
+    The first loss has nothing to be compared with and leaves the rate at r0."""
+    r, falls, out = float(r0), 0, []
+    for i, loss in enumerate(losses):
+        if i > 0:
+            if loss >= losses[i - 1]:
+                r = max(r * 0.5, 1.0)
+                falls = 0
+            else:
+                falls += 1
+                if falls >= u:
+                    r = min(r * 2.0, 100.0)
+                    falls = 0
+        out.append(r)
     return out
 
 

@@ -454,3 +454,119 @@ def test_cfg1_pipeline_shape():
     hs, cs, slots, hoff = O.partition(w.rows, w.batch, [batch.indices[0].numpy()], [None], [remap])
     assert 0.4 * w.batch < hs.size < 0.95 * w.batch
     assert hs.size + cs.size == w.batch
+
+
+# ----------------------------------------------------------------------------------
+# hot <-> full table synchronisation (Sec. 3 (4); Sec. 6.2 "Embedding Synchronization")
+# ----------------------------------------------------------------------------------
+def test_scatter_rows_matches_indexed_assignment_and_round_trips():
+    rng = np.random.default_rng(31)
+    R, dim, n_hot = 300, 12, 77
+    W = rng.standard_normal((R, dim)).astype(np.float32)
+    hot_ids = np.sort(rng.choice(R, n_hot, replace=False)).astype(np.int32)
+    hotW = rng.standard_normal((n_hot, dim)).astype(np.float32)
+    got = O.scatter_rows(W, hot_ids, hotW)
+    ref = W.copy()
+    ref[hot_ids] = hotW                      # numpy's indexed assignment as the library routine
+    assert got.tobytes() == ref.tobytes()
+    cold = np.ones(R, bool)
+    cold[hot_ids] = False
+    assert got[cold].tobytes() == W[cold].tobytes()                      # cold rows untouched
+    assert O.gather_rows(got, hot_ids).tobytes() == hotW.tobytes()       # gather undoes scatter
+    assert O.scatter_rows(W, hot_ids, O.gather_rows(W, hot_ids)).tobytes() == W.tobytes()
+
+
+# ----------------------------------------------------------------------------------
+# hot-size estimate from sampled chunks (Sec. 4.1.2, Eq. 2-4)
+# ----------------------------------------------------------------------------------
+def test_chunk_count_brute_force_and_boundary():
+    rng = np.random.default_rng(32)
+    R, m, H = 1000, 64, 5                    # 16 chunks, the last one holds 40 entries
+    cnt = rng.integers(0, 10, R).astype(np.uint32)
+    chunks = np.arange(16)
+    got = O.chunk_counts(cnt, m, chunks, H)
+    brute = [sum(1 for r in range(i * m, min((i + 1) * m, R)) if cnt[r] >= H) for i in chunks]
+    assert got.tolist() == brute
+    assert int(got.sum()) == O.count_hot(cnt, H)
+    eq = np.full(m, H, dtype=np.uint32)      # k == H is hot (Eq. 2 uses >=)
+    assert O.chunk_counts(eq, m, [0], H).tolist() == [m]
+    assert O.chunk_counts(eq, m, [0], H + 1).tolist() == [0]
+
+
+def test_mean_std_hand_example_and_library():
+    # textbook example: mean 5, sum of squared deviations 32, sample variance 32/7
+    Ci = np.array([2, 4, 4, 4, 5, 5, 7, 9])
+    y, s = O.mean_std(Ci)
+    assert y == 5.0 and abs(s - math.sqrt(32.0 / 7.0)) < 1e-15
+    rng = np.random.default_rng(33)
+    Ci = rng.integers(0, 1025, 35)
+    y, s = O.mean_std(Ci)
+    assert abs(y - np.mean(Ci)) < 1e-12 and abs(s - np.std(Ci, ddof=1)) < 1e-12
+
+
+def test_t_quantiles_match_printed_tables():
+    # two-sided critical values from standard t tables
+    assert abs(O.t_quantile(0.95, 11) - 2.228) < 5e-4        # 10 degrees of freedom
+    assert abs(O.t_quantile(0.99, 21) - 2.845) < 5e-4        # 20 degrees of freedom
+    assert abs(O.t_quantile(0.999, 35) - 3.601) < 5e-4       # n = 35 chunks (Sec. 4.1.2)
+    assert abs(O.t_quantile(0.999, 10 ** 7) - 3.2905) < 5e-4  # normal limit
+
+
+def test_ci_reduces_to_textbook_form_and_vanishes_for_a_census():
+    # N >> n: half-width -> t * s / sqrt(n)
+    hw = O.lib().orc_ci_halfwidth
+    import ctypes as C
+    v = hw(C.c_double(math.sqrt(35.0)), C.c_int64(35), C.c_int64(10 ** 12), C.c_double(3.5))
+    assert abs(v - 3.5) < 1e-9
+    # finite-population factor: sqrt((N - n) / N)
+    v = hw(C.c_double(2.0), C.c_int64(16), C.c_int64(64), C.c_double(1.0))
+    assert abs(v - math.sqrt(48.0 / 64.0) * 2.0 / 4.0) < 1e-15
+    # all N chunks sampled: the estimate is the exact hot count and the interval has no width
+    rng = np.random.default_rng(34)
+    R, m = 10_000, 128
+    cnt = rng.integers(0, 6, R).astype(np.uint32)
+    N = -(-R // m)
+    est, half, _, _ = O.estimate_hot_rows(cnt, m, rng.permutation(N), 3, 0.999)
+    assert abs(est - O.count_hot(cnt, 3)) < 1e-6 and half == 0.0
+
+
+def test_estimate_covers_the_exact_count_and_is_within_ten_percent():
+    """Sec. 4.1.2 with n = 35 chunks of m = 1024 entries and a 99.9 % interval: the exact
+    hot count lies inside the interval for nearly every draw of chunks, and the estimate
+    is within 10 % of it (the paper's Figure on estimated sizes)."""
+    rng = np.random.default_rng(35)
+    R, m, n = 1 << 20, 1024, 35
+    ranks = rng.permutation(R) + 1                       # popularity rank of every row
+    cnt = np.floor(3.0e5 / ranks ** 1.05).astype(np.uint32)
+    H = 3
+    exact = O.count_hot(cnt, H)
+    assert 50_000 < exact < 200_000
+    N = R // m
+    inside = close = 0
+    trials = 200
+    for _ in range(trials):
+        chunks = rng.choice(N, n, replace=False)
+        est, half, _, _ = O.estimate_hot_rows(cnt, m, chunks, H, 0.999)
+        inside += abs(est - exact) <= half
+        close += abs(est - exact) <= 0.10 * exact
+    assert inside >= 0.985 * trials and close >= 0.985 * trials
+
+
+# ----------------------------------------------------------------------------------
+# Shuffle Scheduler (Sec. 5, Eq. 5), u = 4, start at R(50)
+# ----------------------------------------------------------------------------------
+def test_scheduler_hand_worked_sequences():
+    S_ = O.shuffle_scheduler
+    assert S_([1.0]) == [50.0]                                        # starts at R(50)
+    assert S_([1.0, 1.1, 1.2]) == [50.0, 25.0, 12.5]                  # loss rises: halve
+    assert S_([1.0, 1.0]) == [50.0, 25.0]                             # an equal loss is not a fall
+    rising = [float(i) for i in range(12)]
+    assert S_(rising)[-1] == 1.0 and min(S_(rising)) == 1.0           # never below R(1)
+    falling = [10.0 - i for i in range(10)]
+    #          swap: 0     1     2     3     4      5      6      7      8      9
+    assert S_(falling) == [50.0, 50.0, 50.0, 50.0, 100.0, 100.0, 100.0, 100.0, 100.0, 100.0]
+    assert S_(falling, r0=10.0) == [10.0, 10.0, 10.0, 10.0, 20.0, 20.0, 20.0, 20.0, 40.0, 40.0]
+    # three falls, a rise, then four falls: the rise halves and restarts the count
+    seq = [5.0, 4.0, 3.0, 2.0, 2.5, 2.4, 2.3, 2.2, 2.1]
+    assert S_(seq) == [50.0, 50.0, 50.0, 50.0, 25.0, 25.0, 25.0, 25.0, 50.0]
+    assert S_(falling, r0=50.0, u=2) == [50.0, 50.0, 100.0] + [100.0] * 7
