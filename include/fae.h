@@ -120,7 +120,9 @@ int32_t fae_set_option(fae_ctx *ctx, const char *name, int64_t value);
 #define FAE_K_OTHER 12
 #define FAE_K_COPY_PROBE 13  /* plain streaming copy (bandwidth ceiling, counter calibration) */
 #define FAE_K_FWD_SORT 14    /* forward and the backward's LDS sort in one launch */
-#define FAE_K_COUNT 15
+#define FAE_K_SYNC_ROWS 15   /* hot rows <-> full tables                          */
+#define FAE_K_ESTIMATE 16    /* chunk counts of the sampled logger                */
+#define FAE_K_COUNT 17
 int32_t fae_timing_enable(fae_ctx *ctx, int32_t on);
 int32_t fae_timing_reset(fae_ctx *ctx);
 int32_t fae_timing_read(fae_ctx *ctx, int32_t kernel_class, double *h_total_ms, int64_t *h_launches);
@@ -223,6 +225,91 @@ int32_t fae_embbag_fwd_presort(fae_ctx *ctx, const fae_tables *hot_tables, const
 int32_t fae_embbag_bwd_sgd(fae_ctx *ctx, const fae_tables *hot_tables, float *const *h_hotW,
                            const fae_batch *hot_batch, const float *gout, int64_t gout_row_stride,
                            float lr, const fae_bwd_debug *dbg, void *ws, size_t ws_bytes);
+
+/* ---- embedding synchronisation between the hot tables and the full tables ----
+ * (Sec. 3 (4); Sec. 6.2, "Embedding Synchronization") */
+/* When training switches between hot and cold mini-batches the two copies of the hot
+ * rows are brought in line:
+ *   FAE_SYNC_HOT_TO_FULL  W_z[hot_ids_z[s]][:] = hotW_z[s][:]   (before cold mini-batches)
+ *   FAE_SYNC_FULL_TO_HOT  hotW_z[s][:] = W_z[hot_ids_z[s]][:]   (before hot mini-batches)
+ * for s in [0, h_n_hot[z]).  tables describes the full tables (rows_z, dim); h_W[z] is
+ * fp32[rows_z*dim] in memory the device can address (device memory, or pinned host
+ * memory mapped into the device's address space, in which case the host link sets the
+ * rate).  Rows of the destination that are not named stay untouched.  hot_ids_z must not
+ * repeat a row (fae_build_hot_tables never does); an id outside [0, rows_z) is skipped
+ * and reported as FAE_ERANGE by the next synchronising call.  Asynchronous. */
+#define FAE_SYNC_HOT_TO_FULL 0
+#define FAE_SYNC_FULL_TO_HOT 1
+int32_t fae_sync_hot_rows(fae_ctx *ctx, const fae_tables *tables, const int64_t *h_n_hot,
+                          const int32_t *const *h_hot_ids, float *const *h_hotW,
+                          float *const *h_W, int32_t direction);
+
+/* ---- hot-size estimate from sampled chunks of the logger (Sec. 4.1.2, Eq. 2-4) ---- */
+/* The logger of table z is cut into N_z = ceil(rows_z / m) aligned chunks of m entries
+ * (the last one may be short).  The caller draws h_n_chunks[z] distinct chunk numbers
+ * per table (the paper: n = 35 chunks of m = 1024 entries) and passes them in
+ * h_chunks[z] (host int64[h_n_chunks[z]]); the library draws no random numbers.
+ *   C_i   = entries of chunk i with count >= h_cutoff[z]                       (Eq. 2)
+ *   ybar  = mean of the C_i, s = their sample standard deviation (n - 1)       (Eq. 3)
+ *   half  = t_{alpha/2, n-1} * sqrt(((N - n) / N) * s^2 / n), alpha = 1 - confidence  (Eq. 4)
+ * and, scaled to the table, rows = ybar * N_z and half_rows = half * N_z.  A table with a
+ * single sampled chunk has no standard deviation: s and half are reported as 0.
+ * The counting runs on the device (one workgroup per chunk); the statistics of the at
+ * most FAE_MAX_TABLES * n counts are taken on the host in fp64.  h_C_out (optional, host
+ * int32, table after table, h_n_chunks[z] entries each) receives the C_i.  Synchronises. */
+typedef struct {
+    double rows;      /* estimated number of hot rows of the table: ybar * N */
+    double half_rows; /* half-width of its confidence interval, in rows      */
+    double ybar;      /* Eq. 3                                               */
+    double s;         /* sample standard deviation of the chunk counts       */
+    int64_t N;        /* chunks in the table                                 */
+    int64_t n;        /* chunks sampled                                      */
+} fae_hot_estimate;
+size_t fae_estimate_workspace_bytes(const fae_tables *tables, const int64_t *h_n_chunks);
+int32_t fae_estimate_hot(fae_ctx *ctx, const fae_tables *tables, const uint32_t *const *h_counts,
+                         const uint32_t *h_cutoff, int64_t m, const int64_t *h_n_chunks,
+                         const int64_t *const *h_chunks, double confidence,
+                         fae_hot_estimate *h_out /* host [n_tables] */, int32_t *h_C_out,
+                         void *ws, size_t ws_bytes);
+/* Statistical Optimizer (Sec. 4.1.2, "Converging on a Threshold") on the sampled logger:
+ * fae_choose_cutoff with the exact row counts replaced by the estimates above.  Finds the
+ * smallest integer c >= 0 with  sum_z bytes_z(c) <= budget_bytes, where for a table below
+ * small_table_bytes bytes_z = rows_z*dim*4 (wholly hot, not sampled) and otherwise
+ * bytes_z(c) = (sumC_z(c) / n_z) * N_z * (dim*4) in fp64, summed in table order, with
+ * H_z(c) = ceil(c * h_T[z] / t_denom).  The same chunks serve every c, so the estimate
+ * falls monotonically in c and a bisection finds the answer.  h_out receives the estimates
+ * at the chosen c (interval at `confidence`).  Synchronises. */
+int32_t fae_choose_cutoff_sampled(fae_ctx *ctx, const fae_tables *tables, const uint32_t *const *h_counts,
+                                  const int64_t *h_T, int64_t t_denom, int64_t budget_bytes,
+                                  int64_t small_table_bytes, int64_t m, const int64_t *h_n_chunks,
+                                  const int64_t *const *h_chunks, double confidence, int64_t *h_c_out,
+                                  uint32_t *h_cutoff_out, fae_hot_estimate *h_out, void *ws,
+                                  size_t ws_bytes);
+/* Quantile t_{alpha/2} of Student's t distribution with df degrees of freedom for a
+ * two-sided interval of the given confidence (0 < confidence < 1, df >= 1).  Host only. */
+double fae_t_quantile(double confidence, int64_t df);
+
+/* ---- Shuffle Scheduler rate rule (Sec. 5, Eq. 5); host only ------------------- */
+/* The rate R(p), p in [1, 100]: p per cent of the cold (then of the hot) mini-batches
+ * run between two swaps.  After every swap the caller reports the test loss:
+ *   loss >= previous loss                      -> p = max(p / 2, 1)
+ *   loss fell at each of the last u reports    -> p = min(2 p, 100), count starts again
+ *   otherwise                                  -> p unchanged
+ * (the clamps follow the text of Sec. 5: never below R(1), never above R(100)).
+ * fae_sched_init sets p = p0 (the paper starts at R(50)) and u (the paper: 4). */
+typedef struct {
+    double rate;     /* p of R(p)                                 */
+    double prev;     /* loss of the previous report               */
+    int32_t u;       /* successive falls that double the rate     */
+    int32_t falls;   /* successive falls seen since the last change */
+    int32_t reports; /* losses reported so far                    */
+} fae_sched;
+int32_t fae_sched_init(fae_sched *s, double p0, int32_t u);
+/* Returns the rate after taking this loss into account (negative on a bad argument). */
+double fae_sched_report(fae_sched *s, double test_loss);
+/* Mini-batches to run before the next swap at the current rate, out of n_total of that
+ * kind: ceil(p / 100 * n_total), at least 1 (0 if n_total is 0). */
+int64_t fae_sched_segment(const fae_sched *s, int64_t n_total);
 
 #ifdef __cplusplus
 }

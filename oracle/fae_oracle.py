@@ -179,6 +179,30 @@ def estimate_hot_rows(cnt: np.ndarray, m: int, chunks: np.ndarray, H: int, confi
     return ybar * N, hw * N, ybar, s
 
 
+def sampled_budget_cutoff(dim: int, cnts: List[np.ndarray], T: Sequence[int], t_denom: int, budget_bytes: int,
+                          small_table_bytes: int, m: int, chunks: Sequence[Sequence[int]], c_limit: int = 1 << 20):
+    """Statistical Optimizer on the sampled logger (Sec. 4.1.2, "Converging on a Threshold"):
+    the budget rule of ``budget_cutoff`` with every sampled table's exact hot-row count
+    replaced by its estimate ybar * N (Eq. 2, Eq. 3).  Scans c = 0, 1, 2, ... and returns the
+    first (c, H[z]) whose estimated bytes fit; tables below small_table_bytes are wholly hot."""
+    row_bytes = dim * 4
+    for c in range(c_limit):
+        total, H = 0.0, []
+        for z, cnt in enumerate(cnts):
+            if cnt.size * row_bytes < small_table_bytes:
+                H.append(0)
+                total += float(cnt.size) * float(row_bytes)
+                continue
+            h = min(-(-(c * int(T[z])) // int(t_denom)), 4294967295)
+            H.append(h)
+            ybar, _ = mean_std(chunk_counts(cnt, m, chunks[z], h))
+            N = -(-cnt.size // m)
+            total += ybar * float(N) * float(row_bytes)
+        if total <= float(budget_bytes):
+            return c, H
+    raise OracleError(ENOSPC, "sampled_budget_cutoff: no threshold below c_limit fits")
+
+
 def shuffle_scheduler(losses: Sequence[float], r0: float = 50.0, u: int = 4) -> List[float]:
     """Shuffle Scheduler (Sec. 5, Eq. 5): the rate after each swap, given the test loss
     measured after each swap.  Rates are the p of R(p), kept inside [1, 100].

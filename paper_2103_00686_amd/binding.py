@@ -18,6 +18,7 @@ LIB_PATH = os.path.join(_PKG, "libfae.so")
 FAE_OK, FAE_EINVAL, FAE_ERANGE, FAE_ENOSPC, FAE_EHIP = 0, -1, -2, -3, -4
 FAE_MAX_TABLES = 64
 FAE_SRC_DEVICE, FAE_SRC_PROCEDURAL = 0, 1
+FAE_SYNC_HOT_TO_FULL, FAE_SYNC_FULL_TO_HOT = 0, 1
 
 EXPORTS = [
     "fae_create", "fae_destroy", "fae_last_error", "fae_version", "fae_sync", "fae_set_option",
@@ -27,6 +28,8 @@ EXPORTS = [
     "fae_partition_batch", "fae_embbag_fwd", "fae_bwd_workspace_bytes", "fae_embbag_bwd_presort",
     "fae_embbag_fwd_presort",
     "fae_embbag_bwd_sgd",
+    "fae_sync_hot_rows", "fae_estimate_workspace_bytes", "fae_estimate_hot", "fae_choose_cutoff_sampled",
+    "fae_t_quantile", "fae_sched_init", "fae_sched_report", "fae_sched_segment",
 ]
 
 
@@ -53,6 +56,16 @@ class _BwdDebug(C.Structure):
     _fields_ = [("uniq", C.c_void_p), ("runlen", C.c_void_p), ("table_start", C.c_void_p)]
 
 
+class _HotEstimate(C.Structure):
+    _fields_ = [("rows", C.c_double), ("half_rows", C.c_double), ("ybar", C.c_double), ("s", C.c_double),
+                ("N", C.c_int64), ("n", C.c_int64)]
+
+
+class _Sched(C.Structure):
+    _fields_ = [("rate", C.c_double), ("prev", C.c_double), ("u", C.c_int32), ("falls", C.c_int32),
+                ("reports", C.c_int32)]
+
+
 _lib = None
 
 
@@ -71,10 +84,17 @@ def load():
     lib.fae_last_error.argtypes = [C.c_void_p]
     lib.fae_version.restype = C.c_char_p
     for name in ("fae_choose_cutoff_workspace_bytes", "fae_build_workspace_bytes",
-                 "fae_partition_workspace_bytes", "fae_bwd_workspace_bytes"):
+                 "fae_partition_workspace_bytes", "fae_bwd_workspace_bytes", "fae_estimate_workspace_bytes"):
         getattr(lib, name).restype = C.c_size_t
     lib.fae_destroy.restype = None
     lib.fae_kernel_name.restype = C.c_char_p
+    lib.fae_t_quantile.restype = C.c_double
+    lib.fae_t_quantile.argtypes = [C.c_double, C.c_int64]
+    lib.fae_sched_report.restype = C.c_double
+    lib.fae_sched_report.argtypes = [C.c_void_p, C.c_double]
+    lib.fae_sched_init.argtypes = [C.c_void_p, C.c_double, C.c_int32]
+    lib.fae_sched_segment.restype = C.c_int64
+    lib.fae_sched_segment.argtypes = [C.c_void_p, C.c_int64]
     _lib = lib
     return lib
 
@@ -184,7 +204,7 @@ def fae_set_option(ctx: Context, name: str, value: int):
     ctx.check(load().fae_set_option(ctx._h, name.encode(), C.c_int64(value)))
 
 
-FAE_K_COUNT = 15
+FAE_K_COUNT = 17
 
 
 def fae_kernel_name(kernel_class: int) -> str:
@@ -331,3 +351,96 @@ def fae_embbag_bwd_sgd(ctx: Context, hot_tables: Tables, hotW: List[torch.Tensor
     ctx.check(load().fae_embbag_bwd_sgd(ctx._h, C.byref(t), _ptrs(hotW, torch.float32), C.byref(b),
                                         _ptr(gout, torch.float32), C.c_int64(gout_row_stride), C.c_float(lr),
                                         dbg, _ptr(ws, torch.uint8), C.c_size_t(ws.numel())))
+
+
+def fae_sync_hot_rows(ctx: Context, tables: Tables, n_hot: Sequence[int], hot_ids: List[torch.Tensor],
+                      hotW: List[torch.Tensor], W: List[torch.Tensor], direction: int):
+    nt = len(tables.rows)
+    t = tables.c()
+    nh = (C.c_int64 * nt)(*[int(v) for v in n_hot])
+    ctx.check(load().fae_sync_hot_rows(ctx._h, C.byref(t), nh, _ptrs(hot_ids, torch.int32),
+                                       _ptrs(hotW, torch.float32), _ptrs(W, torch.float32), C.c_int32(direction)))
+
+
+def _chunk_args(chunks: Sequence[Sequence[int]]):
+    nt = len(chunks)
+    n = (C.c_int64 * nt)(*[len(c) for c in chunks])
+    arrs = [(C.c_int64 * max(len(c), 1))(*[int(v) for v in c]) for c in chunks]
+    ptrs = (C.c_void_p * nt)(*[C.cast(a, C.c_void_p) for a in arrs])
+    return n, ptrs, arrs
+
+
+def fae_estimate_workspace_bytes(tables: Tables, n_chunks: Sequence[int]) -> int:
+    t = tables.c()
+    n = (C.c_int64 * len(n_chunks))(*[int(v) for v in n_chunks])
+    return int(load().fae_estimate_workspace_bytes(C.byref(t), n))
+
+
+def _estimates(out, nt):
+    return [dict(rows=out[z].rows, half_rows=out[z].half_rows, ybar=out[z].ybar, s=out[z].s,
+                 N=int(out[z].N), n=int(out[z].n)) for z in range(nt)]
+
+
+def fae_estimate_hot(ctx: Context, tables: Tables, counts: List[torch.Tensor], cutoff: Sequence[int], m: int,
+                     chunks: Sequence[Sequence[int]], confidence: float, ws: torch.Tensor):
+    """Returns (estimates[z] as dicts, C[z] lists of chunk counts)."""
+    nt = len(tables.rows)
+    t = tables.c()
+    cut = (C.c_uint32 * nt)(*[int(v) for v in cutoff])
+    n, ptrs, keep = _chunk_args(chunks)
+    out = (_HotEstimate * nt)()
+    total = sum(len(c) for c in chunks)
+    Cout = (C.c_int32 * max(total, 1))()
+    ctx.check(load().fae_estimate_hot(ctx._h, C.byref(t), _ptrs(counts, torch.int32), cut, C.c_int64(m), n, ptrs,
+                                      C.c_double(confidence), out, Cout, _ptr(ws, torch.uint8),
+                                      C.c_size_t(ws.numel())))
+    Cs, pos = [], 0
+    for c in chunks:
+        Cs.append(list(Cout[pos:pos + len(c)]))
+        pos += len(c)
+    return _estimates(out, nt), Cs
+
+
+def fae_choose_cutoff_sampled(ctx: Context, tables: Tables, counts: List[torch.Tensor], T: Sequence[int],
+                              t_denom: int, budget_bytes: int, small_table_bytes: int, m: int,
+                              chunks: Sequence[Sequence[int]], confidence: float, ws: torch.Tensor):
+    """Returns (c, cutoff[z], estimates[z])."""
+    nt = len(tables.rows)
+    t = tables.c()
+    Ta = (C.c_int64 * nt)(*[int(v) for v in T])
+    n, ptrs, keep = _chunk_args(chunks)
+    c_out = C.c_int64(0)
+    cut = (C.c_uint32 * nt)()
+    out = (_HotEstimate * nt)()
+    ctx.check(load().fae_choose_cutoff_sampled(ctx._h, C.byref(t), _ptrs(counts, torch.int32), Ta, C.c_int64(t_denom),
+                                               C.c_int64(budget_bytes), C.c_int64(small_table_bytes), C.c_int64(m),
+                                               n, ptrs, C.c_double(confidence), C.byref(c_out), cut, out,
+                                               _ptr(ws, torch.uint8), C.c_size_t(ws.numel())))
+    return int(c_out.value), list(cut), _estimates(out, nt)
+
+
+def fae_t_quantile(confidence: float, df: int) -> float:
+    return float(load().fae_t_quantile(C.c_double(confidence), C.c_int64(df)))
+
+
+class Sched:
+    """fae_sched and its three calls (host only; needs no GPU)."""
+
+    def __init__(self, p0: float = 50.0, u: int = 4):
+        self._s = _Sched()
+        rc = load().fae_sched_init(C.byref(self._s), C.c_double(p0), C.c_int32(u))
+        if rc != FAE_OK:
+            raise FaeError(rc, "fae_sched_init: bad argument")
+
+    @property
+    def rate(self) -> float:
+        return float(self._s.rate)
+
+    def report(self, test_loss: float) -> float:
+        r = float(load().fae_sched_report(C.byref(self._s), C.c_double(test_loss)))
+        if r < 0:
+            raise FaeError(FAE_EINVAL, "fae_sched_report: bad argument")
+        return r
+
+    def segment(self, n_total: int) -> int:
+        return int(load().fae_sched_segment(C.byref(self._s), C.c_int64(n_total)))

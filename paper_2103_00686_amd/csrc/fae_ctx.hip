@@ -195,7 +195,7 @@ extern "C" const char *fae_kernel_name(int32_t k)
     static const char *names[FAE_K_COUNT] = {"fwd",        "bwd_keys",  "sort_hist", "sort_colscan", "sort_scatter",
                                              "bwd_reduce", "bwd_fixup", "lds_sort",  "fill",         "profile",
                                              "partition",  "build",     "other",     "copy_probe",
-                                             "fwd_sort"};
+                                             "fwd_sort",   "sync_rows", "estimate"};
     return (k >= 0 && k < FAE_K_COUNT) ? names[k] : "?";
 }
 

@@ -122,6 +122,26 @@ class HotPath:
         ws = self._workspace("cut", B.fae_choose_cutoff_workspace_bytes(self.tables))
         return B.fae_count_hot(self.ctx, self.tables, self.counts, cutoff, ws)
 
+    # -- sampled estimate of the hot size (Sec. 4.1.2, Eq. 2-4) ----------------------
+    def estimate_hot(self, cutoff: Sequence[int], chunks: Sequence[Sequence[int]], m: int = 1024,
+                     confidence: float = 0.999):
+        ws = self._workspace("est", B.fae_estimate_workspace_bytes(self.tables, [len(c) for c in chunks]))
+        return B.fae_estimate_hot(self.ctx, self.tables, self.counts, cutoff, m, chunks, confidence, ws)
+
+    def choose_cutoff_sampled(self, budget_bytes: int, chunks: Sequence[Sequence[int]], m: int = 1024,
+                              confidence: float = 0.999, small_table_bytes: int = 1 << 20):
+        ws = self._workspace("est", B.fae_estimate_workspace_bytes(self.tables, [len(c) for c in chunks]))
+        return B.fae_choose_cutoff_sampled(self.ctx, self.tables, self.counts, self.profiled_lookups,
+                                           max(max(self.profiled_lookups), 1), budget_bytes, small_table_bytes,
+                                           m, chunks, confidence, ws)
+
+    # -- hot <-> full table synchronisation (Sec. 3 (4), Sec. 6.2) -----------------------
+    def sync_to_full(self, W: List[torch.Tensor]):
+        B.fae_sync_hot_rows(self.ctx, self.tables, self.n_hot, self.hot_ids, self.hotW, W, B.FAE_SYNC_HOT_TO_FULL)
+
+    def sync_from_full(self, W: List[torch.Tensor]):
+        B.fae_sync_hot_rows(self.ctx, self.tables, self.n_hot, self.hot_ids, self.hotW, W, B.FAE_SYNC_FULL_TO_HOT)
+
     # -- a3 + a4 --------------------------------------------------------------------
     def build(self, cutoff: Sequence[int], n_hot: Sequence[int], src_W: Optional[List[torch.Tensor]] = None,
               seed: int = 0) -> List[int]:

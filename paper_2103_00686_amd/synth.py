@@ -394,6 +394,16 @@ def _draw_rows(w: Workload, z: int, pos: torch.Tensor, kidx: int, kperm: int, de
     return permute_rows(ranks - 1, w.rows[z], kperm)
 
 
+def sample_chunks(w: "Workload", z: int, m: int, n: int, draw: int = 0) -> List[int]:
+    """n distinct chunk numbers out of the ceil(rows_z / m) aligned chunks of table z's
+    logger (all of them if there are fewer than n): the first n values of a keyed
+    bijection.  Inputs of the sampled hot-size estimate; no arithmetic of the method."""
+    N = -(-w.rows[z] // m)
+    k = min(n, N)
+    key = stream_key(w.seed, 7001, draw, z)
+    return [int(v) for v in permute_rows(torch.arange(k, dtype=torch.int64), N, key).tolist()]
+
+
 def upstream_grads(w: Workload, stream: int, n_samples: int, device: str | torch.device = "cpu") -> torch.Tensor:
     """N(0,1) gradient of the loss w.r.t. the pooled outputs, fp32[S][Tn][dim]."""
     return normal_f32((n_samples, w.n_tables, w.dim), stream_key(w.seed, w.cfg_id, stream, 7), device)

@@ -570,3 +570,18 @@ def test_scheduler_hand_worked_sequences():
     seq = [5.0, 4.0, 3.0, 2.0, 2.5, 2.4, 2.3, 2.2, 2.1]
     assert S_(seq) == [50.0, 50.0, 50.0, 50.0, 25.0, 25.0, 25.0, 25.0, 50.0]
     assert S_(falling, r0=50.0, u=2) == [50.0, 50.0, 100.0] + [100.0] * 7
+
+
+def test_sampled_budget_search_with_a_census_equals_the_exact_search():
+    """With every chunk of every table sampled the estimate is the exact hot count, so the
+    sampled search must pick the same c and cutoffs as the exact budget rule (Sec. 4.1)."""
+    rng = np.random.default_rng(36)
+    dim, m = 8, 64
+    cnts = [rng.zipf(1.4, r).astype(np.uint32) for r in (3000, 1280, 700)]
+    T = [int(c.sum()) for c in cnts]
+    t_denom = max(T)
+    chunks = [list(rng.permutation(-(-c.size // m))) for c in cnts]
+    for budget in (30_000, 60_000, 200_000):
+        c_ref, H_ref, _ = O.budget_cutoff(dim, cnts, T, t_denom, budget, small_table_bytes=25_000)
+        c, H = O.sampled_budget_cutoff(dim, cnts, T, t_denom, budget, 25_000, m, chunks)
+        assert (c, list(H)) == (c_ref, [int(h) for h in H_ref])
