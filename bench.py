@@ -253,6 +253,32 @@ def run_workload(args, cfg_id, n_steps, n_warmup, with_cpu):
     roofline["step_frac_of_copy_ceiling"] = round((bytes_fwd + bytes_bwd) / (ms_per_step * 1e-3) / 1e9 / copy_gbps, 4)
     del src, dst
 
+    # ---- steps around the path: sampled hot-size estimate, embedding synchronisation -------
+    chunks = [S.sample_chunks(w, z, 1024, 35) for z in range(nt)]
+    hp.estimate_hot(H, chunks, 1024, 0.999)
+    (est, _), dt = timed(lambda: hp.estimate_hot(H, chunks, 1024, 0.999))
+    stages["estimate_call_us"] = dt * 1e6
+    stages["estimate_rel_err"] = (sum(e["rows"] for e in est) - sum(n_hot)) / max(sum(n_hot), 1)
+    stages["estimate_ci_rel_halfwidth"] = sum(e["half_rows"] for e in est) / max(sum(n_hot), 1)
+    if w.hot_rule != "cutoff":
+        (c_s, H_s, _), dt = timed(lambda: hp.choose_cutoff_sampled(w.budget_bytes, chunks, 1024, 0.999, w.small_table_bytes))
+        stages["cutoff_sampled_ms"] = dt * 1e3
+        stages["cutoff_sampled_c"] = c_s
+    if sum(w.rows) * D * 4 <= (64 << 30):    # full tables that fit beside the hot set (contents do not matter here)
+        full = [torch.empty((r, D), dtype=torch.float32, device=dev) for r in w.rows]
+        sync_bytes = sum(n_hot) * (2 * D * 4 + 4)
+        for name, fn in (("sync_to_full_GBps", hp.sync_to_full), ("sync_from_full_GBps", hp.sync_from_full)):
+            fn(full)
+            B.fae_timing_enable(hp.ctx, True)
+            B.fae_timing_reset(hp.ctx)
+            for _ in range(5):
+                fn(full)
+            ms, n = B.fae_timing_read(hp.ctx, 15)
+            B.fae_timing_enable(hp.ctx, False)
+            stages[name] = sync_bytes / (ms / n * 1e-3) / 1e9
+        stages["sync_bytes"] = sync_bytes
+        del full
+
     # ---- the oracle on the host, bounded sample ----------------------------------------
     cpu = None
     if with_cpu:
