@@ -249,6 +249,16 @@ def run_workload(args, cfg_id, n_steps, n_warmup, with_cpu):
     B.fae_timing_enable(hp.ctx, False)
     copy_gbps = 2 * src.numel() * 4 / (ms / n * 1e-3) / 1e9
     roofline["copy_ceiling_GBps"] = round(copy_gbps, 1)
+    sink = torch.zeros(4, dtype=torch.float32, device=dev)
+    for _ in range(3):
+        B.fae_read_probe(hp.ctx, src, sink)
+    B.fae_timing_enable(hp.ctx, True)
+    B.fae_timing_reset(hp.ctx)
+    for _ in range(10):
+        B.fae_read_probe(hp.ctx, src, sink)
+    ms, n = B.fae_timing_read(hp.ctx, 17)
+    B.fae_timing_enable(hp.ctx, False)
+    roofline["read_ceiling_GBps"] = round(src.numel() * 4 / (ms / n * 1e-3) / 1e9, 1)
     roofline["frac_of_copy_ceiling"] = round(dom_gbps / copy_gbps, 4)
     roofline["step_frac_of_copy_ceiling"] = round((bytes_fwd + bytes_bwd) / (ms_per_step * 1e-3) / 1e9 / copy_gbps, 4)
     del src, dst

@@ -98,7 +98,10 @@ int32_t fae_sync(fae_ctx *ctx);
 /* Tuning/ablation switches, e.g. ("profile_variant", 0=auto 1=global atomics
  * 2=LDS-privatised), ("fwd_variant", 0=auto 1=group-per-bag 2=wave-per-bag),
  * ("sort_variant", 0=auto, 1=global radix with three kernels per pass, 2=LDS per table
- * where it fits, 3=global radix with one kernel per pass). */
+ * where it fits, 3=global radix with one kernel per pass), ("reduce_variant", 0=auto
+ * 1=segmented scan across lane groups 2=a share of the span per lane group),
+ * ("reduce_span", 0/64/128/256 sorted lookups per wave), ("reduce_unroll", 0/4/8 gradient
+ * rows in flight per lane group, second form only), ("fwd_stream_out", 0/1). */
 int32_t fae_set_option(fae_ctx *ctx, const char *name, int64_t value);
 
 /* ---- per-kernel timing (measurement aid; off by default) ---------------------- */
@@ -122,7 +125,8 @@ int32_t fae_set_option(fae_ctx *ctx, const char *name, int64_t value);
 #define FAE_K_FWD_SORT 14    /* forward and the backward's LDS sort in one launch */
 #define FAE_K_SYNC_ROWS 15   /* hot rows <-> full tables                          */
 #define FAE_K_ESTIMATE 16    /* chunk counts of the sampled logger                */
-#define FAE_K_COUNT 17
+#define FAE_K_READ_PROBE 17  /* plain streaming read (read-only bandwidth ceiling)      */
+#define FAE_K_COUNT 18
 int32_t fae_timing_enable(fae_ctx *ctx, int32_t on);
 int32_t fae_timing_reset(fae_ctx *ctx);
 int32_t fae_timing_read(fae_ctx *ctx, int32_t kernel_class, double *h_total_ms, int64_t *h_launches);
@@ -131,6 +135,11 @@ const char *fae_kernel_name(int32_t kernel_class);
  * kernel: what a bandwidth-bound kernel can reach on this device, and a transfer of known
  * size against which hardware byte counters are scaled.  Asynchronous. */
 int32_t fae_copy_probe(fae_ctx *ctx, void *dst, const void *src, size_t bytes);
+/* The same access pattern, reading only: `bytes` (multiple of 16) of src are loaded and
+ * summed; nothing is stored unless the sum has one particular value, in which case one float
+ * goes to sink[0] (so the loads cannot be dropped).  What a read-dominated kernel can reach
+ * on this device.  Asynchronous. */
+int32_t fae_read_probe(fae_ctx *ctx, const void *src, size_t bytes, float *sink);
 
 /* ---- a1: Embedding Logger (Sec. 4.1.2) ------------------------------------- */
 /* counts_z[r] += number of lookups of `chunk` into row r of table z.  The caller

@@ -556,6 +556,186 @@ template <typename V, int LPR> __global__ __launch_bounds__(256) void bwd_reduce
     }
 }
 
+// Segment reduce + SGD, second form: no traffic between lanes while the gradient rows are
+// summed.  A wave still owns a span of sorted lookups, but each of its 64/LPR lane groups walks
+// its own contiguous share of the span: NB gradient rows in flight per group and a running sum
+// per run.  The (slot, sample) pairs are fetched one batch ahead (the same address in all lanes
+// of a group), so the shape of the runs is known when a batch's loads are issued: the weight
+// row of every run that closes strictly inside the share is loaded together with the gradient
+// rows and updated as soon as the run's sum is complete.  What is left per group is its first
+// and its last run; one pass over the groups, in order, joins those that continue each other
+// and sends every joined run to its place: the weight row (preloaded by the group in which the
+// run ends), or the span's head / tail scratch row when the run crosses the span's border (the
+// fix-up kernel adds those up in span order, so the result does not depend on timing).
+template <typename V, int LPR, int NB> __global__ __launch_bounds__(256) void bwd_reduce_walk_kernel(BwdArgs a)
+{
+    constexpr int G = FAE_WAVE / LPR;
+    constexpr int VW = sizeof(V) / sizeof(float);
+    const int sid = blockIdx.x * (256 / FAE_WAVE) + threadIdx.x / FAE_WAVE;
+    if (sid >= a.n_spans)
+        return;
+    const SpanInfo sp = bwd_span_info(a, sid);
+    const int lane = fae_lane(), g = lane / LPR, l = lane % LPR;
+    const int ncols = a.dim / VW;
+    const int n_hot = a.n_hot[sp.z];
+    V *W = (V *)a.W[sp.z];
+    const float *gbase = a.gout + (int64_t)sp.z * a.dim;
+    V *part = (V *)(a.partial + (int64_t)sid * 2 * a.dim);
+    const int share = a.span / G; // lookups per group (the span is a multiple of 64)
+    const int q0 = sp.pos0 + g * share < sp.pos1 ? sp.pos0 + g * share : sp.pos1;
+    const int q1 = q0 + share < sp.pos1 ? q0 + share : sp.pos1;
+
+    for (int c0 = 0; c0 < ncols; c0 += LPR) {
+        const int c = c0 + l;
+        const bool active = c < ncols;
+        // NB pairs of a batch and the key that follows them; KEY_NONE past the share's end
+        auto load_pairs = [&](int j0, int *kk, int *ss) {
+            if (NB % 4 == 0 && (j0 & 3) == 0 && j0 + NB <= q1) {
+#pragma unroll
+                for (int u = 0; u < NB; u += 4) {
+                    const int4 k4 = *(const int4 *)(a.keys_in + j0 + u);
+                    const int4 s4 = *(const int4 *)(a.vals_in + j0 + u);
+                    kk[u] = k4.x; kk[u + 1] = k4.y; kk[u + 2] = k4.z; kk[u + 3] = k4.w;
+                    ss[u] = s4.x; ss[u + 1] = s4.y; ss[u + 2] = s4.z; ss[u + 3] = s4.w;
+                }
+            } else {
+#pragma unroll
+                for (int u = 0; u < NB; ++u) {
+                    kk[u] = j0 + u < q1 ? a.keys_in[j0 + u] : KEY_NONE;
+                    ss[u] = j0 + u < q1 ? a.vals_in[j0 + u] : 0;
+                }
+            }
+            kk[NB] = j0 + NB < q1 ? a.keys_in[j0 + NB] : KEY_NONE;
+        };
+        int cur = KEY_NONE;  // key of the run being summed
+        V acc = bwd_vec<V>::zero();
+        int hk = KEY_NONE;   // the share's first run, once it has closed inside the share
+        V hv = bwd_vec<V>::zero();
+        bool multi = false;  // a run has closed inside the share
+        bool multi_ahead = false; // the same, as of the batch whose loads are being issued
+        int kn[NB + 1], sn[NB];
+        load_pairs(q0, kn, sn);
+        for (int j0 = q0; j0 < q1; j0 += NB) {
+            int kk[NB + 1], ss[NB];
+#pragma unroll
+            for (int u = 0; u < NB; ++u) {
+                kk[u] = kn[u];
+                ss[u] = sn[u];
+            }
+            kk[NB] = kn[NB];
+            V vv[NB], ww[NB];
+            bool closes[NB];
+            if (j0 + NB <= q1 && active) {
+                // a full batch: every load is issued without a branch around it (a lookup that needs no
+                // weight row reads row 0 of the table, a line that stays in the cache), and the
+                // running sums are kept with selects instead of branches
+#pragma unroll
+                for (int u = 0; u < NB; ++u) {
+                    vv[u] = ((const V *)(gbase + (int64_t)ss[u] * a.gout_stride))[c];
+                    closes[u] = kk[u + 1] != KEY_NONE && kk[u + 1] != kk[u];
+                    const bool need_w = closes[u] && multi_ahead && kk[u] < n_hot;
+                    ww[u] = W[(int64_t)(need_w ? kk[u] : 0) * ncols + c];
+                    multi_ahead = multi_ahead || closes[u];
+                }
+                load_pairs(j0 + NB, kn, sn);
+#pragma unroll
+                for (int u = 0; u < NB; ++u) {
+                    const bool same = kk[u] == cur;
+                    V t = vv[u];
+                    if (same)
+                        bwd_vec<V>::add(t, acc);
+                    acc = t;
+                    cur = kk[u];
+                    const bool first_close = closes[u] && !multi;
+                    if (first_close) {
+                        hk = cur;
+                        hv = acc;
+                    }
+                    if (closes[u] && multi && cur < n_hot)
+                        W[(int64_t)cur * ncols + c] = bwd_vec<V>::sgd(ww[u], acc, a.lr);
+                    multi = multi || closes[u];
+                }
+                continue;
+            }
+#pragma unroll
+            for (int u = 0; u < NB; ++u) {
+                vv[u] = (active && kk[u] != KEY_NONE) ? ((const V *)(gbase + (int64_t)ss[u] * a.gout_stride))[c]
+                                                     : bwd_vec<V>::zero();
+                // a run closes here if another key follows inside the share
+                closes[u] = kk[u] != KEY_NONE && kk[u + 1] != KEY_NONE && kk[u + 1] != kk[u];
+                const bool need_w = closes[u] && multi_ahead && active && kk[u] < n_hot;
+                ww[u] = need_w ? W[(int64_t)kk[u] * ncols + c] : bwd_vec<V>::zero();
+                multi_ahead = multi_ahead || closes[u];
+            }
+            load_pairs(j0 + NB, kn, sn); // past the share's end it loads nothing
+#pragma unroll
+            for (int u = 0; u < NB; ++u) {
+                const int k = kk[u];
+                if (k == KEY_NONE)
+                    continue;
+                if (k == cur) {
+                    bwd_vec<V>::add(acc, vv[u]);
+                } else {
+                    cur = k;
+                    acc = vv[u];
+                }
+                if (closes[u]) {
+                    if (!multi) {
+                        hk = cur;
+                        hv = acc;
+                        multi = true;
+                    } else if (active && cur < n_hot) {
+                        W[(int64_t)cur * ncols + c] = bwd_vec<V>::sgd(ww[u], acc, a.lr);
+                    }
+                }
+            }
+        }
+        // weight rows of the group's first and last run, for whichever joined run ends there
+        const V wh = (multi && active && hk < n_hot) ? W[(int64_t)hk * ncols + c] : bwd_vec<V>::zero();
+        const V wt = (cur != KEY_NONE && active && cur < n_hot) ? W[(int64_t)cur * ncols + c] : bwd_vec<V>::zero();
+        // a joined run with key k and sum v that ends in group `at` (as its first run if head)
+        auto flush = [&](int at, bool head, int k, const V &v) {
+            if (g != at || !active || k >= n_hot)
+                return;
+            if (sp.head_open && k == sp.first_key)
+                part[c] = v;
+            else if (sp.tail_open && k == sp.last_key)
+                part[ncols + c] = v;
+            else
+                W[(int64_t)k * ncols + c] = bwd_vec<V>::sgd(head ? wh : wt, v, a.lr);
+        };
+        int ck = KEY_NONE, gprev = 0;
+        V cv = bwd_vec<V>::zero();
+#pragma unroll
+        for (int gp = 0; gp < G; ++gp) {
+            const int e_tk = __builtin_amdgcn_readlane(cur, gp * LPR);
+            if (e_tk == KEY_NONE)
+                continue; // an empty share (only past the span's end)
+            const int e_multi = __builtin_amdgcn_readlane((int)multi, gp * LPR);
+            const int e_hk = __builtin_amdgcn_readlane(hk, gp * LPR);
+            const V e_tv = bwd_shfl<V>(acc, gp * LPR + l);
+            const V e_hv = bwd_shfl<V>(hv, gp * LPR + l);
+            const int fk = e_multi ? e_hk : e_tk; // key of the share's first run
+            V first = e_multi ? e_hv : e_tv;
+            if (fk == ck)
+                bwd_vec<V>::add(first, cv); // continues the run carried over from the shares before
+            else if (ck != KEY_NONE)
+                flush(gprev, false, ck, cv);
+            if (e_multi) {
+                flush(gp, true, fk, first);
+                ck = e_tk;
+                cv = e_tv;
+            } else {
+                ck = fk;
+                cv = first;
+            }
+            gprev = gp;
+        }
+        if (ck != KEY_NONE)
+            flush(gprev, false, ck, cv);
+    }
+}
+
 // one wave per span: if a run starts in this span and continues past its end, add the
 // pieces (this span's tail, the following spans' heads) and apply the update.  The lanes
 // find the extent of the run together (64 following spans per ballot) and the lane groups
@@ -753,7 +933,13 @@ template <typename V, int LPR> void launch_reduce(fae_ctx *ctx, const BwdArgs &a
 {
     {
         fae_ktimer kt(ctx, FAE_K_BWD_REDUCE);
-        hipLaunchKernelGGL((bwd_reduce_kernel<V, LPR>), dim3((a.n_spans + 3) / 4), dim3(256), 0, ctx->stream, a);
+        const dim3 grid((a.n_spans + 3) / 4);
+        if (ctx->opt_reduce != 2)
+            hipLaunchKernelGGL((bwd_reduce_kernel<V, LPR>), grid, dim3(256), 0, ctx->stream, a);
+        else if (ctx->opt_unroll == 8)
+            hipLaunchKernelGGL((bwd_reduce_walk_kernel<V, LPR, 8>), grid, dim3(256), 0, ctx->stream, a);
+        else
+            hipLaunchKernelGGL((bwd_reduce_walk_kernel<V, LPR, 4>), grid, dim3(256), 0, ctx->stream, a);
     }
     fae_ktimer kt(ctx, FAE_K_BWD_FIXUP);
     hipLaunchKernelGGL((bwd_fixup_kernel<V, LPR>), dim3((a.n_spans + 3) / 4), dim3(256), 0, ctx->stream, a);

@@ -195,7 +195,7 @@ extern "C" const char *fae_kernel_name(int32_t k)
     static const char *names[FAE_K_COUNT] = {"fwd",        "bwd_keys",  "sort_hist", "sort_colscan", "sort_scatter",
                                              "bwd_reduce", "bwd_fixup", "lds_sort",  "fill",         "profile",
                                              "partition",  "build",     "other",     "copy_probe",
-                                             "fwd_sort",   "sync_rows", "estimate"};
+                                             "fwd_sort",   "sync_rows", "estimate",  "read_probe"};
     return (k >= 0 && k < FAE_K_COUNT) ? names[k] : "?";
 }
 
@@ -217,6 +217,10 @@ extern "C" int32_t fae_set_option(fae_ctx *ctx, const char *name, int64_t value)
         ctx->opt_fwd_stream = value;
     else if (!strcmp(name, "reduce_span") && (value == 0 || value == 64 || value == 128 || value == 256))
         ctx->opt_span = value;
+    else if (!strcmp(name, "reduce_variant") && value >= 0 && value <= 2)
+        ctx->opt_reduce = value;
+    else if (!strcmp(name, "reduce_unroll") && (value == 0 || value == 4 || value == 8))
+        ctx->opt_unroll = value;
     else
         return fae_fail(ctx, FAE_EINVAL, "fae_set_option: unknown option or value: %s=%lld", name,
                         (long long)value);

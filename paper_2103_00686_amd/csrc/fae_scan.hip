@@ -61,6 +61,47 @@ __global__ __launch_bounds__(256) void fae_copy_probe_kernel(float4 *dst, const 
         dst[i] = src[i];
 }
 
+__global__ __launch_bounds__(256) void fae_read_probe_kernel(const float4 *src, int64_t n, float *sink)
+{
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (; i + 3 * stride < n; i += 4 * stride) {
+        const float4 a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
+        s.x += (a.x + b.x) + (c.x + d.x);
+        s.y += (a.y + b.y) + (c.y + d.y);
+        s.z += (a.z + b.z) + (c.z + d.z);
+        s.w += (a.w + b.w) + (c.w + d.w);
+    }
+    for (; i < n; i += stride) {
+        const float4 a = src[i];
+        s.x += a.x;
+        s.y += a.y;
+        s.z += a.z;
+        s.w += a.w;
+    }
+    if ((s.x + s.y) + (s.z + s.w) == 1.2345678e-30f)
+        sink[0] = s.x;
+}
+
+extern "C" int32_t fae_read_probe(fae_ctx *ctx, const void *src, size_t bytes, float *sink)
+{
+    if (!ctx || !src || !sink || bytes % 16 != 0 || ((uintptr_t)src) % 16 != 0)
+        return fae_fail(ctx, FAE_EINVAL, "fae_read_probe: null or misaligned argument");
+    const int64_t n = (int64_t)(bytes / 16);
+    if (n == 0)
+        return FAE_OK;
+    int64_t blocks = (n + 255) / 256;
+    const int64_t cap = (int64_t)ctx->n_cu * 32;
+    if (blocks > cap)
+        blocks = cap;
+    fae_ktimer kt(ctx, FAE_K_READ_PROBE);
+    hipLaunchKernelGGL(fae_read_probe_kernel, dim3((unsigned)blocks), dim3(256), 0, ctx->stream, (const float4 *)src, n,
+                       sink);
+    FAE_LAUNCH_CHECK(ctx);
+    return FAE_OK;
+}
+
 extern "C" int32_t fae_copy_probe(fae_ctx *ctx, void *dst, const void *src, size_t bytes)
 {
     if (!ctx || !dst || !src || bytes % 16 != 0 || ((uintptr_t)dst) % 16 != 0 || ((uintptr_t)src) % 16 != 0)

@@ -45,6 +45,24 @@ def test_workload_end_to_end(dev, cfg_id, materialise):
     p.check_backward(batches[-1], stream=24)                        # sorted pairs of another batch: not used
 
 
+@pytest.mark.parametrize("cfg_id", [2, 3, 5])
+@pytest.mark.parametrize("reduce_variant,unroll,span", [(1, 0, 0), (2, 0, 0), (2, 4, 64), (2, 8, 256), (2, 8, 128)])
+def test_reduce_variants(dev, cfg_id, reduce_variant, unroll, span):
+    """Both forms of the segment reduce, every load depth and span length, on one-hot and
+    multi-hot workloads; two steps, so the second sees rows the first has changed."""
+    w = S.workload(cfg_id, "test")
+    p = T.Pipeline(w, dev, profile_chunks=1)
+    for k, v in (("reduce_variant", reduce_variant), ("reduce_unroll", unroll), ("reduce_span", span)):
+        B.fae_set_option(p.hp.ctx, k, v)
+    p.check_profile()
+    p.check_cutoff()
+    p.check_build()
+    batches = T.hot_batches(p, 2)
+    p.check_backward(batches[0], stream=30)
+    p.check_backward(batches[-1], stream=31)
+    p.check_forward(batches[0], exact_gather=False)
+
+
 @pytest.mark.parametrize("variant", [1, 2])
 def test_profile_variants_agree_with_oracle(dev, variant):
     w = S.workload(2, "test")
@@ -62,6 +80,7 @@ def test_forward_backward_shapes(dev, variant, dim):
     n_hot, S_ = [700, 3, 1], 333
     hp = HotPath(n_hot, dim, 0)
     B.fae_set_option(hp.ctx, "fwd_variant", variant)
+    B.fae_set_option(hp.ctx, "reduce_variant", variant)     # both forms of the segment reduce see every shape
     hp.n_hot = n_hot
     Wref = [(rng.random((n, dim), dtype=np.float32) - 0.5) for n in n_hot]
     hp.hotW = [torch.from_numpy(x).to(dev) for x in Wref]
@@ -97,8 +116,9 @@ def test_forward_backward_shapes(dev, variant, dim):
         assert got[mask].tobytes() == before[z][mask].tobytes()
 
 
-@pytest.mark.parametrize("S_,sort_variant", [(50_000, 0), (50_000, 1), (50_000, 3), (300_000, 0), (300_000, 1)])
-def test_backward_long_runs_and_many_tiles(dev, S_, sort_variant):
+@pytest.mark.parametrize("S_,sort_variant,reduce_variant", [(50_000, 0, 1), (50_000, 1, 2), (50_000, 3, 2), (300_000, 0, 2),
+                                                            (300_000, 1, 1), (50_000, 0, 2)])
+def test_backward_long_runs_and_many_tiles(dev, S_, sort_variant, reduce_variant):
     """One slot repeated tens of thousands of times (a run that crosses hundreds of spans and, in
     the key-range sort, a single value larger than the LDS buffers), runs of about two spans,
     several sort tiles, three radix passes.  50 000 lookups take the key-range sort (or the
@@ -116,6 +136,7 @@ def test_backward_long_runs_and_many_tiles(dev, S_, sort_variant):
     rows = np.unique(slots)
     hp = HotPath([n_hot], dim, 0)
     B.fae_set_option(hp.ctx, "sort_variant", sort_variant)
+    B.fae_set_option(hp.ctx, "reduce_variant", reduce_variant)
     hp.n_hot = [n_hot]
     hp.hotW = [torch.zeros((n_hot, dim), dtype=torch.float32, device=dev)]
     w_rows = (rng.random((rows.size, dim), dtype=np.float32) - 0.5)
