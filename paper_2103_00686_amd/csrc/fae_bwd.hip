@@ -491,8 +491,11 @@ template <typename V, int LPR> __global__ __launch_bounds__(256) void bwd_reduce
     for (int c0 = 0; c0 < ncols; c0 += LPR) {
         const int c = c0 + l;
         const bool active = c < ncols;
-        int ck = KEY_NONE; // key of the run still open at the end of the previous step
+        // Sum of the run that is open at the end of the previous step.  It lives in the last lane
+        // group only: the rotations of the scan below hand it to the groups that continue the run.
         V cv = bwd_vec<V>::zero();
+        int klast = KEY_NONE; // last key of the previous tile (none at the span's start)
+        int dist_in = 0;      // position inside its run of a lookup that continues the previous tile's last run
         for (int t0 = sp.pos0; t0 < sp.pos1; t0 += FAE_WAVE) {
             const int p = t0 + lane;
             const int kreg = p < sp.pos1 ? a.keys_in[p] : KEY_NONE;
@@ -508,6 +511,19 @@ template <typename V, int LPR> __global__ __launch_bounds__(256) void bwd_reduce
             int dreg = 0;
             if (p < sp.pos1 && kafter != kreg && kreg < n_hot)
                 dreg = (sp.head_open && kreg == sp.first_key) ? 2 : ((sp.tail_open && kreg == sp.last_key) ? 3 : 1);
+            // dist = how many lookups of the same run precede lookup p inside this span (capped):
+            // lookup p continues the sum of lookup p - d exactly when dist >= d, so the scan needs
+            // no key comparisons across lanes.  From the run heads of the tile (one ballot).
+            int kprev = __shfl_up(kreg, 1, FAE_WAVE);
+            if (lane == 0)
+                kprev = klast;
+            const uint64_t heads = __ballot(kreg != kprev);
+            const uint64_t upto = heads & (lane == FAE_WAVE - 1 ? ~0ull : ((2ull << lane) - 1ull));
+            int dist = upto != 0 ? lane - (63 - __clzll(upto)) : lane + dist_in;
+            dist = dist < 255 ? dist : 255;
+            dreg |= dist << 2;
+            klast = __builtin_amdgcn_readlane(kreg, FAE_WAVE - 1);
+            dist_in = __builtin_amdgcn_readlane(dist, FAE_WAVE - 1) + 1;
             for (int i0 = 0; i0 < STEPS; i0 += UN) {
                 if (t0 + i0 * G >= sp.pos1)
                     break;
@@ -521,35 +537,34 @@ template <typename V, int LPR> __global__ __launch_bounds__(256) void bwd_reduce
                     const int s = __shfl(sreg, e, FAE_WAVE);
                     vv[u] = (active && kk[u] != KEY_NONE) ? ((const V *)(gbase + (int64_t)s * a.gout_stride))[c]
                                                          : bwd_vec<V>::zero();
-                    ww[u] = (active && dd[u] == 1) ? W[(int64_t)kk[u] * ncols + c] : bwd_vec<V>::zero();
+                    ww[u] = (active && (dd[u] & 3) == 1) ? W[(int64_t)kk[u] * ncols + c] : bwd_vec<V>::zero();
                 }
 #pragma unroll
                 for (int u = 0; u < UN; ++u) {
                     const int kg = kk[u];
+                    const int dest = dd[u] & 3, dist_u = dd[u] >> 2;
                     V vg = vv[u];
-                    // inclusive segmented scan over the lane groups (equal keys are adjacent)
+                    // Inclusive segmented scan over the lane groups, the open run of the previous step
+                    // standing in front of group 0: a rotation by d groups brings group g - d to
+                    // group g, and the carried sum (held by the last group) to group d - 1.
 #pragma unroll
                     for (int d = 1; d < G; d <<= 1) {
-                        const int kp = __shfl_up(kg, d * LPR, FAE_WAVE);
-                        const V vp = bwd_shfl_up<V>(vg, d * LPR);
-                        if (g >= d && kp == kg)
+                        const V z = g == G - 1 ? cv : vg;
+                        const V vp = bwd_shfl<V>(z, (lane - d * LPR) & (FAE_WAVE - 1));
+                        if (dist_u >= d && g >= d - 1)
                             bwd_vec<V>::add(vg, vp);
                     }
-                    if (kg == ck)
-                        bwd_vec<V>::add(vg, cv); // the run was already open before this step
+                    if (g == G - 1 && dist_u >= G)
+                        bwd_vec<V>::add(vg, cv); // the last group reaches back past group 0
                     if (active) {
-                        if (dd[u] == 1)
+                        if (dest == 1)
                             W[(int64_t)kg * ncols + c] = bwd_vec<V>::sgd(ww[u], vg, a.lr);
-                        else if (dd[u] == 2)
+                        else if (dest == 2)
                             part[c] = vg;
-                        else if (dd[u] == 3)
+                        else if (dest == 3)
                             part[ncols + c] = vg;
                     }
-                    // the last group's run stays open unless it just ended
-                    const int last_k = __shfl(kg, (G - 1) * LPR + l, FAE_WAVE);
-                    const int last_d = __shfl(dd[u], (G - 1) * LPR + l, FAE_WAVE);
-                    cv = bwd_shfl<V>(vg, (G - 1) * LPR + l);
-                    ck = (last_d != 0 || last_k >= n_hot) ? KEY_NONE : last_k;
+                    cv = vg; // used from the last group only
                 }
             }
         }
