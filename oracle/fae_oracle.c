@@ -454,3 +454,87 @@ int orc_embbag_bwd_sgd(int64_t n_hot, int32_t dim, float *hotW,
     free(Ga);
     return ORC_OK;
 }
+
+
+/* ------------------------------------------------------------------ */
+/* Variants the paper leaves open (Sec. 2.2 names the pooled lookup    */
+/* and the optimizer step without fixing either): mean pooling and a   */
+/* row-wise Adagrad optimizer.                                         */
+/* ------------------------------------------------------------------ */
+
+/* Mean pooling: the sum of the bag's rows (with multiplicity) divided by the
+ * number of lookups in the bag; an empty bag gives zeros.  mag (optional)
+ * receives sum |term| / len for the tolerance. */
+int orc_embbag_fwd_mean(int64_t n_hot, int32_t dim, const float *hotW,
+                        int64_t n_samples, const int32_t *slots,
+                        const int32_t *offsets, float *out, int64_t out_stride,
+                        double *mag, int64_t mag_stride)
+{
+    for (int64_t s = 0; s < n_samples; ++s) {
+        int64_t b = offsets ? offsets[s] : s;
+        int64_t e = offsets ? offsets[s + 1] : s + 1;
+        for (int32_t c = 0; c < dim; ++c) {
+            double acc = 0.0, m = 0.0;
+            for (int64_t j = b; j < e; ++j) {
+                if (slots[j] < 0 || (int64_t)slots[j] >= n_hot)
+                    return ORC_ERANGE;
+                double v = (double)hotW[(int64_t)slots[j] * dim + c];
+                acc += v;
+                m += fabs(v);
+            }
+            if (e > b) {
+                acc /= (double)(e - b);
+                m /= (double)(e - b);
+            }
+            out[s * out_stride + c] = (float)acc;
+            if (mag)
+                mag[s * mag_stride + c] = m;
+        }
+    }
+    return ORC_OK;
+}
+
+/* Gradient of a row under mean pooling: every lookup of a bag of len lookups
+ * receives the bag's upstream gradient divided by len.  Same arguments as
+ * orc_run_grads plus bag_len[s]. */
+void orc_run_grads_mean(const int32_t *order, const int32_t *bag_of,
+                        const int32_t *bag_len, const int64_t *run_start,
+                        const int32_t *runlen, const int64_t *sel,
+                        int64_t n_sel, const float *gout, int64_t gout_stride,
+                        int32_t dim, double *G, double *Gabs)
+{
+    for (int64_t i = 0; i < n_sel; ++i) {
+        int64_t u = sel[i];
+        for (int32_t c = 0; c < dim; ++c) {
+            double acc = 0.0, m = 0.0;
+            for (int64_t p = run_start[u]; p < run_start[u] + runlen[u]; ++p) {
+                int32_t s = bag_of[order[p]];
+                double g = (double)gout[(int64_t)s * gout_stride + c] / (double)bag_len[s];
+                acc += g;
+                m += fabs(g);
+            }
+            G[i * dim + c] = acc;
+            if (Gabs)
+                Gabs[i * dim + c] = m;
+        }
+    }
+}
+
+/* Row-wise Adagrad on n rows, one accumulator per row: the accumulator grows by
+ * the mean over the row's elements of the squared gradient, and the row moves
+ * by lr * G / (sqrt(accumulator) + eps).  Computed in double, rounded once. */
+void orc_rowwise_adagrad_rows(float *W_rows, float *state, const double *G,
+                              float lr, float eps, int64_t n, int32_t dim)
+{
+    for (int64_t i = 0; i < n; ++i) {
+        double ms = 0.0;
+        for (int32_t c = 0; c < dim; ++c)
+            ms += G[i * dim + c] * G[i * dim + c];
+        ms /= (double)dim;
+        double acc = (double)state[i] + ms;
+        double scale = (double)lr / (sqrt(acc) + (double)eps);
+        state[i] = (float)acc;
+        for (int32_t c = 0; c < dim; ++c)
+            W_rows[i * dim + c] = (float)((double)W_rows[i * dim + c] - scale * G[i * dim + c]);
+    }
+}

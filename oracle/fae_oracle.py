@@ -359,3 +359,89 @@ def embbag_bwd_sgd(hotW: List[np.ndarray], n_samples: int, slots: List[np.ndarra
         runlen_l.append(runlen[:U].copy())
         mag_l.append(None if mag is None else mag[:U].copy())
     return uniq_l, runlen_l, mag_l
+
+
+# -- variants the paper leaves open: mean pooling, row-wise Adagrad ------------------------
+POOL_SUM, POOL_MEAN = 0, 1
+OPT_SGD, OPT_ROWWISE_ADAGRAD = 0, 1
+
+
+def embbag_fwd_mean(hotW: List[np.ndarray], n_samples: int, slots: List[np.ndarray],
+                    offsets: List[Optional[np.ndarray]], want_mag: bool = False):
+    """Mean-pooled forward, same layout as ``embbag_fwd``."""
+    nt = len(hotW)
+    dim = hotW[0].shape[1]
+    out = np.zeros((n_samples, nt, dim), dtype=np.float32)
+    mag = np.zeros((n_samples, nt, dim), dtype=np.float64) if want_mag else None
+    for z in range(nt):
+        W = _arr(hotW[z], np.float32)
+        s = _arr(slots[z], np.int32)
+        o = None if offsets[z] is None else _arr(offsets[z], np.int32)
+        oz = out[:, z, :]
+        mz = mag[:, z, :] if want_mag else None
+        rc = lib().orc_embbag_fwd_mean(C.c_int64(W.shape[0]), C.c_int32(dim), _p(W), C.c_int64(n_samples),
+                                       _p(s), _p(o), C.c_void_p(oz.ctypes.data), C.c_int64(nt * dim),
+                                       None if mz is None else C.c_void_p(mz.ctypes.data), C.c_int64(nt * dim))
+        _check(rc, "embbag_fwd_mean")
+    return (out, mag) if want_mag else out
+
+
+def bag_len(offsets: Optional[np.ndarray], n_samples: int) -> np.ndarray:
+    if offsets is None:
+        return np.ones(n_samples, dtype=np.int32)
+    return np.diff(_arr(offsets, np.int32)).astype(np.int32)
+
+
+def run_grads_mean(order: np.ndarray, bag: np.ndarray, blen: np.ndarray, runlen: np.ndarray, sel: np.ndarray,
+                   gout: np.ndarray, table: int):
+    """``run_grads`` under mean pooling (each lookup receives its bag's gradient / bag length)."""
+    gout = _arr(gout, np.float32)
+    _, nt, dim = gout.shape
+    order, bag, blen, runlen = (_arr(x, np.int32) for x in (order, bag, blen, runlen))
+    sel = _arr(sel, np.int64)
+    run_start = np.zeros(runlen.size + 1, dtype=np.int64)
+    np.cumsum(runlen, out=run_start[1:])
+    G = np.zeros((sel.size, dim), dtype=np.float64)
+    Ga = np.zeros((sel.size, dim), dtype=np.float64)
+    base = gout.ctypes.data + table * dim * 4
+    lib().orc_run_grads_mean(_p(order), _p(bag), _p(blen), _p(run_start), _p(runlen), _p(sel), C.c_int64(sel.size),
+                             C.c_void_p(base), C.c_int64(nt * dim), C.c_int32(dim), _p(G), _p(Ga))
+    return G, Ga
+
+
+def rowwise_adagrad_rows(W_rows: np.ndarray, state: np.ndarray, G: np.ndarray, lr: float, eps: float):
+    """Returns (new rows, new accumulators); inputs are not modified."""
+    W = _arr(W_rows, np.float32).copy()
+    st = _arr(state, np.float32).copy()
+    G = _arr(G, np.float64)
+    lib().orc_rowwise_adagrad_rows(_p(W), _p(st), _p(G), C.c_float(lr), C.c_float(eps), C.c_int64(W.shape[0]),
+                                   C.c_int32(W.shape[1]))
+    return W, st
+
+
+def embbag_bwd_opts(hotW: List[np.ndarray], state: Optional[List[np.ndarray]], n_samples: int,
+                    slots: List[np.ndarray], offsets: List[Optional[np.ndarray]], gout: np.ndarray,
+                    lr: float, eps: float = 0.0, pooling: int = POOL_SUM, optimizer: int = OPT_SGD):
+    """Backward + optimizer with the chosen pooling and optimizer, in place on hotW[z] (and
+    state[z] for Adagrad).  Returns per table (uniq, runlen, G fp64[U][dim], Gabs, w_old rows,
+    state_old of the touched rows)."""
+    res = []
+    for z, W in enumerate(hotW):
+        assert W.dtype == np.float32 and W.flags.c_contiguous
+        s = _arr(slots[z], np.int32)
+        order, uniq, runlen = sort_runs(s)
+        bag = bag_of(offsets[z], n_samples, s.size)
+        sel = np.arange(uniq.size)
+        if pooling == POOL_MEAN:
+            G, Ga = run_grads_mean(order, bag, bag_len(offsets[z], n_samples), runlen, sel, gout, z)
+        else:
+            G, Ga = run_grads(order, bag, runlen, sel, gout, z)
+        w_old = W[uniq].copy()
+        st_old = None
+        if optimizer == OPT_ROWWISE_ADAGRAD:
+            st_old = state[z][uniq].copy()
+            W[uniq], state[z][uniq] = rowwise_adagrad_rows(w_old, st_old, G, lr, eps)
+        else:
+            W[uniq] = sgd_rows(w_old, G, lr)
+        res.append((uniq, runlen, G, Ga, w_old, st_old))
+    return res

@@ -585,3 +585,90 @@ def test_sampled_budget_search_with_a_census_equals_the_exact_search():
         c_ref, H_ref, _ = O.budget_cutoff(dim, cnts, T, t_denom, budget, small_table_bytes=25_000)
         c, H = O.sampled_budget_cutoff(dim, cnts, T, t_denom, budget, 25_000, m, chunks)
         assert (c, list(H)) == (c_ref, [int(h) for h in H_ref])
+
+
+# ----------------------------------------------------------------------------------
+# variants the paper leaves open: mean pooling, row-wise Adagrad
+# ----------------------------------------------------------------------------------
+def _ragged(rng, S_, n_hot, max_len):
+    lens = rng.integers(0, max_len + 1, S_)
+    o = np.zeros(S_ + 1, dtype=np.int32)
+    o[1:] = np.cumsum(lens)
+    return rng.integers(0, n_hot, int(o[-1])).astype(np.int32), o
+
+
+def test_mean_forward_hand_example_and_torch_black_box():
+    W = np.array([[1.0, 10.0], [2.0, 20.0], [6.0, 60.0]], dtype=np.float32)
+    slots = np.array([0, 2, 2, 1], dtype=np.int32)
+    offs = np.array([0, 3, 3, 4], dtype=np.int32)          # bags: {0,2,2}, {}, {1}
+    out = O.embbag_fwd_mean([W], 3, [slots], [offs])
+    assert np.allclose(out[:, 0, :], [[13 / 3, 130 / 3], [0, 0], [2, 20]], rtol=1e-7, atol=0)
+    rng = np.random.default_rng(41)
+    n_hot, dim, S_ = 50, 7, 200
+    W = rng.standard_normal((n_hot, dim)).astype(np.float32)
+    slots, offs = _ragged(rng, S_, n_hot, 9)
+    ref = torch.nn.functional.embedding_bag(torch.from_numpy(slots.astype(np.int64)), torch.from_numpy(W),
+                                            torch.from_numpy(offs[:-1].astype(np.int64)), mode="mean").numpy()
+    got = O.embbag_fwd_mean([W], S_, [slots], [offs])[:, 0, :]
+    assert np.allclose(got, ref, rtol=2e-6, atol=1e-6)
+    one_hot = O.embbag_fwd_mean([W], 5, [slots[:5]], [None])[:, 0, :]       # bags of one lookup: a plain gather
+    assert one_hot.tobytes() == W[slots[:5]].tobytes()
+
+
+def test_mean_backward_matches_autograd():
+    rng = np.random.default_rng(42)
+    n_hot, dim, S_ = 40, 5, 150
+    W = rng.standard_normal((n_hot, dim)).astype(np.float32)
+    slots, offs = _ragged(rng, S_, n_hot, 6)
+    gout = rng.standard_normal((S_, 1, dim)).astype(np.float32)
+    Wt = torch.from_numpy(W.copy()).requires_grad_(True)
+    out = torch.nn.functional.embedding_bag(torch.from_numpy(slots.astype(np.int64)), Wt,
+                                            torch.from_numpy(offs[:-1].astype(np.int64)), mode="mean")
+    out.backward(torch.from_numpy(gout[:, 0, :]))
+    dense = Wt.grad.numpy()
+    order, uniq, runlen = O.sort_runs(slots)
+    G, Ga = O.run_grads_mean(order, O.bag_of(offs, S_, slots.size), O.bag_len(offs, S_), runlen,
+                             np.arange(uniq.size), gout, 0)
+    assert np.allclose(G, dense[uniq], rtol=1e-5, atol=1e-6)
+    untouched = np.ones(n_hot, bool)
+    untouched[uniq] = False
+    assert not dense[untouched].any()
+    assert (Ga >= np.abs(G) - 1e-12).all()
+
+
+def test_rowwise_adagrad_hand_example_and_library_for_dim_one():
+    # G = (3, 4): mean square 12.5; accumulator 0 -> 12.5; step lr / (sqrt(12.5) + eps)
+    W, st = O.rowwise_adagrad_rows(np.array([[1.0, 1.0]], np.float32), np.zeros(1, np.float32),
+                                   np.array([[3.0, 4.0]]), lr=0.1, eps=0.5)
+    scale = 0.1 / (math.sqrt(12.5) + 0.5)
+    assert abs(float(st[0]) - 12.5) < 1e-6
+    assert np.allclose(W, [[1 - 3 * scale, 1 - 4 * scale]], rtol=1e-7)
+    # with one element per row the rule is the element-wise Adagrad of the library
+    rng = np.random.default_rng(43)
+    n = 30
+    w = rng.standard_normal((n, 1)).astype(np.float32)
+    p = torch.from_numpy(w.copy()).requires_grad_(True)
+    opt = torch.optim.Adagrad([p], lr=0.05, eps=1e-3, initial_accumulator_value=0.0)
+    st = np.zeros(n, np.float32)
+    for step in range(3):
+        g = rng.standard_normal((n, 1)).astype(np.float32)
+        p.grad = torch.from_numpy(g.copy())
+        opt.step()
+        w, st = O.rowwise_adagrad_rows(w, st, g.astype(np.float64), 0.05, 1e-3)
+        assert np.allclose(w, p.detach().numpy(), rtol=1e-5, atol=1e-6)
+    # lr = 0 leaves the rows, the accumulators still grow
+    w2, st2 = O.rowwise_adagrad_rows(w, st, np.ones((n, 1)), 0.0, 1e-3)
+    assert w2.tobytes() == w.tobytes() and np.allclose(st2, st + 1.0)
+
+
+def test_backward_variants_driver_reduces_to_plain_sgd():
+    """embbag_bwd_opts with sum pooling and SGD is the path already pinned above."""
+    rng = np.random.default_rng(44)
+    n_hot, dim, S_ = 60, 4, 120
+    W = rng.standard_normal((n_hot, dim)).astype(np.float32)
+    slots, offs = _ragged(rng, S_, n_hot, 5)
+    gout = rng.standard_normal((S_, 1, dim)).astype(np.float32)
+    A, B_ = [W.copy()], [W.copy()]
+    O.embbag_bwd_sgd(A, S_, [slots], [offs], gout, 0.1)
+    O.embbag_bwd_opts(B_, None, S_, [slots], [offs], gout, 0.1)
+    assert A[0].tobytes() == B_[0].tobytes()
