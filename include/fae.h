@@ -235,6 +235,36 @@ int32_t fae_embbag_bwd_sgd(fae_ctx *ctx, const fae_tables *hot_tables, float *co
                            const fae_batch *hot_batch, const float *gout, int64_t gout_row_stride,
                            float lr, const fae_bwd_debug *dbg, void *ws, size_t ws_bytes);
 
+/* ---- pooling and optimizer variants ----------------------------------------------
+ * The paper names the pooled embedding lookup and the optimizer step (Sec. 2.2) without
+ * fixing either; fae_embbag_fwd / fae_embbag_bwd_sgd are sum pooling and plain SGD.  These
+ * entry points add the two other choices common in recommender training:
+ *   FAE_POOL_MEAN   out = (sum of the bag's rows) / (lookups in the bag); an empty bag gives
+ *                   zeros; in the backward every lookup receives its bag's gradient / length.
+ *   FAE_OPT_ROWWISE_ADAGRAD   one fp32 accumulator per hot row (h_state[z] -> device
+ *                   fp32[n_hot_z], zero before the first step).  Per distinct row of a step,
+ *                   with G the summed gradient of the row:
+ *                     acc += (1/dim) * sum_c G[c]^2;  w[c] -= lr * G[c] / (sqrt(acc) + eps).
+ *                   Needs dim <= 256 (dim <= 64 when dim % 4 != 0).
+ * With FAE_POOL_SUM and FAE_OPT_SGD they are the plain calls.  Asynchronous. */
+#define FAE_POOL_SUM 0
+#define FAE_POOL_MEAN 1
+#define FAE_OPT_SGD 0
+#define FAE_OPT_ROWWISE_ADAGRAD 1
+typedef struct {
+    int32_t pooling;
+    int32_t optimizer;
+    float lr;
+    float eps;             /* FAE_OPT_ROWWISE_ADAGRAD only */
+    float *const *h_state; /* FAE_OPT_ROWWISE_ADAGRAD only */
+} fae_step_opts;
+int32_t fae_embbag_fwd_opts(fae_ctx *ctx, const fae_tables *hot_tables, const float *const *h_hotW,
+                            const fae_batch *hot_batch, float *out, int64_t out_row_stride,
+                            const fae_step_opts *opts);
+int32_t fae_embbag_bwd_opts(fae_ctx *ctx, const fae_tables *hot_tables, float *const *h_hotW,
+                            const fae_batch *hot_batch, const float *gout, int64_t gout_row_stride,
+                            const fae_step_opts *opts, const fae_bwd_debug *dbg, void *ws, size_t ws_bytes);
+
 /* ---- embedding synchronisation between the hot tables and the full tables ----
  * (Sec. 3 (4); Sec. 6.2, "Embedding Synchronization") */
 /* When training switches between hot and cold mini-batches the two copies of the hot

@@ -19,6 +19,8 @@ FAE_OK, FAE_EINVAL, FAE_ERANGE, FAE_ENOSPC, FAE_EHIP = 0, -1, -2, -3, -4
 FAE_MAX_TABLES = 64
 FAE_SRC_DEVICE, FAE_SRC_PROCEDURAL = 0, 1
 FAE_SYNC_HOT_TO_FULL, FAE_SYNC_FULL_TO_HOT = 0, 1
+FAE_POOL_SUM, FAE_POOL_MEAN = 0, 1
+FAE_OPT_SGD, FAE_OPT_ROWWISE_ADAGRAD = 0, 1
 
 EXPORTS = [
     "fae_create", "fae_destroy", "fae_last_error", "fae_version", "fae_sync", "fae_set_option",
@@ -30,6 +32,7 @@ EXPORTS = [
     "fae_embbag_bwd_sgd",
     "fae_sync_hot_rows", "fae_estimate_workspace_bytes", "fae_estimate_hot", "fae_choose_cutoff_sampled",
     "fae_t_quantile", "fae_sched_init", "fae_sched_report", "fae_sched_segment",
+    "fae_embbag_fwd_opts", "fae_embbag_bwd_opts",
 ]
 
 
@@ -59,6 +62,11 @@ class _BwdDebug(C.Structure):
 class _HotEstimate(C.Structure):
     _fields_ = [("rows", C.c_double), ("half_rows", C.c_double), ("ybar", C.c_double), ("s", C.c_double),
                 ("N", C.c_int64), ("n", C.c_int64)]
+
+
+class _StepOpts(C.Structure):
+    _fields_ = [("pooling", C.c_int32), ("optimizer", C.c_int32), ("lr", C.c_float), ("eps", C.c_float),
+                ("h_state", C.POINTER(C.c_void_p))]
 
 
 class _Sched(C.Structure):
@@ -356,6 +364,38 @@ def fae_embbag_bwd_sgd(ctx: Context, hot_tables: Tables, hotW: List[torch.Tensor
     ctx.check(load().fae_embbag_bwd_sgd(ctx._h, C.byref(t), _ptrs(hotW, torch.float32), C.byref(b),
                                         _ptr(gout, torch.float32), C.c_int64(gout_row_stride), C.c_float(lr),
                                         dbg, _ptr(ws, torch.uint8), C.c_size_t(ws.numel())))
+
+
+def _step_opts(pooling: int, optimizer: int, lr: float, eps: float, state: Optional[List[torch.Tensor]]):
+    sp = _ptrs(state, torch.float32) if state is not None else None
+    o = _StepOpts(int(pooling), int(optimizer), float(lr), float(eps), sp)
+    o._keep = sp
+    return o
+
+
+def fae_embbag_fwd_opts(ctx: Context, hot_tables: Tables, hotW: List[torch.Tensor], hot_batch: Batch,
+                        out: torch.Tensor, out_row_stride: int, pooling: int):
+    t, b = hot_tables.c(), hot_batch.c()
+    o = _step_opts(pooling, FAE_OPT_SGD, 0.0, 0.0, None)
+    ctx.check(load().fae_embbag_fwd_opts(ctx._h, C.byref(t), _ptrs(hotW, torch.float32), C.byref(b),
+                                         _ptr(out, torch.float32), C.c_int64(out_row_stride), C.byref(o)))
+
+
+def fae_embbag_bwd_opts(ctx: Context, hot_tables: Tables, hotW: List[torch.Tensor], hot_batch: Batch,
+                        gout: torch.Tensor, gout_row_stride: int, lr: float, ws: torch.Tensor,
+                        pooling: int = FAE_POOL_SUM, optimizer: int = FAE_OPT_SGD, eps: float = 0.0,
+                        state: Optional[List[torch.Tensor]] = None,
+                        dbg_uniq: Optional[torch.Tensor] = None, dbg_runlen: Optional[torch.Tensor] = None,
+                        dbg_table_start: Optional[torch.Tensor] = None):
+    t, b = hot_tables.c(), hot_batch.c()
+    o = _step_opts(pooling, optimizer, lr, eps, state)
+    dbg = None
+    if dbg_uniq is not None:
+        d = _BwdDebug(_ptr(dbg_uniq, torch.int32), _ptr(dbg_runlen, torch.int32), _ptr(dbg_table_start, torch.int32))
+        dbg = C.byref(d)
+    ctx.check(load().fae_embbag_bwd_opts(ctx._h, C.byref(t), _ptrs(hotW, torch.float32), C.byref(b),
+                                         _ptr(gout, torch.float32), C.c_int64(gout_row_stride), C.byref(o),
+                                         dbg, _ptr(ws, torch.uint8), C.c_size_t(ws.numel())))
 
 
 def fae_sync_hot_rows(ctx: Context, tables: Tables, n_hot: Sequence[int], hot_ids: List[torch.Tensor],

@@ -51,6 +51,11 @@ struct BwdArgs {
     int32_t *ticket;   // [SWEEP_MAX_PASSES] next tile to hand out, per pass
     int32_t *ghist;    // [n_tables][SWEEP_MAX_PASSES][RADIX] digit counts of a table, per pass
     uint32_t *state;   // [SWEEP_MAX_PASSES][total_tiles][RADIX] flag (2 bits) | count (30 bits)
+    // pooling / optimizer variants
+    int32_t mean;      // every lookup receives its bag's gradient divided by the bag's length
+    int32_t adagrad;   // row-wise Adagrad instead of plain SGD
+    float eps;
+    float *opt_state[FAE_MAX_TABLES]; // Adagrad: one accumulator per hot row
     const float *gout;
     int64_t gout_stride;
     float lr;
@@ -171,6 +176,8 @@ __global__ __launch_bounds__(256) void bwd_keys_kernel(BwdArgs a)
         }
     }
 }
+
+static_assert(sizeof(BwdArgs) <= 4096, "kernel arguments are passed by value");
 
 // ---------------------------------------------------------------------------------
 // 2. segmented LSD radix sort, one pass = histogram / column scan / scatter
@@ -424,11 +431,21 @@ template <> struct bwd_vec<float4> {
     {
         return make_float4(w.x - lr * g.x, w.y - lr * g.y, w.z - lr * g.z, w.w - lr * g.w);
     }
+    static __device__ __forceinline__ void scale(float4 &a, float f)
+    {
+        a.x *= f;
+        a.y *= f;
+        a.z *= f;
+        a.w *= f;
+    }
+    static __device__ __forceinline__ float sumsq(const float4 &a) { return (a.x * a.x + a.y * a.y) + (a.z * a.z + a.w * a.w); }
 };
 template <> struct bwd_vec<float> {
     static __device__ __forceinline__ float zero() { return 0.f; }
     static __device__ __forceinline__ void add(float &a, const float &b) { a += b; }
     static __device__ __forceinline__ float sgd(const float &w, const float &g, float lr) { return w - lr * g; }
+    static __device__ __forceinline__ void scale(float &a, float f) { a *= f; }
+    static __device__ __forceinline__ float sumsq(const float &a) { return a * a; }
 };
 
 template <typename V> __device__ __forceinline__ V bwd_shfl_up(const V &v, int d);
@@ -522,6 +539,12 @@ template <typename V, int LPR> __global__ __launch_bounds__(256) void bwd_reduce
             int dist = upto != 0 ? lane - (63 - __clzll(upto)) : lane + dist_in;
             dist = dist < 255 ? dist : 255;
             dreg |= dist << 2;
+            float ireg = 1.0f; // mean pooling: 1 / (lookups in the lookup's bag)
+            if (a.mean && a.offsets[sp.z] && p < sp.pos1) {
+                const int32_t *off = a.offsets[sp.z];
+                const int len = off[sreg + 1] - off[sreg];
+                ireg = 1.0f / (float)(len > 0 ? len : 1);
+            }
             klast = __builtin_amdgcn_readlane(kreg, FAE_WAVE - 1);
             dist_in = __builtin_amdgcn_readlane(dist, FAE_WAVE - 1) + 1;
             for (int i0 = 0; i0 < STEPS; i0 += UN) {
@@ -529,21 +552,26 @@ template <typename V, int LPR> __global__ __launch_bounds__(256) void bwd_reduce
                     break;
                 int kk[UN], dd[UN];
                 V vv[UN], ww[UN];
+                float inv[UN], sw[UN];
 #pragma unroll
                 for (int u = 0; u < UN; ++u) { // every load of the batch is issued before the first use
                     const int e = (i0 + u) * G + g;
                     kk[u] = __shfl(kreg, e, FAE_WAVE);
                     dd[u] = __shfl(dreg, e, FAE_WAVE);
                     const int s = __shfl(sreg, e, FAE_WAVE);
+                    inv[u] = a.mean ? __shfl(ireg, e, FAE_WAVE) : 1.0f;
                     vv[u] = (active && kk[u] != KEY_NONE) ? ((const V *)(gbase + (int64_t)s * a.gout_stride))[c]
                                                          : bwd_vec<V>::zero();
                     ww[u] = (active && (dd[u] & 3) == 1) ? W[(int64_t)kk[u] * ncols + c] : bwd_vec<V>::zero();
+                    sw[u] = (a.adagrad && (dd[u] & 3) == 1) ? a.opt_state[sp.z][kk[u]] : 0.f;
                 }
 #pragma unroll
                 for (int u = 0; u < UN; ++u) {
                     const int kg = kk[u];
                     const int dest = dd[u] & 3, dist_u = dd[u] >> 2;
                     V vg = vv[u];
+                    if (a.mean)
+                        bwd_vec<V>::scale(vg, inv[u]);
                     // Inclusive segmented scan over the lane groups, the open run of the previous step
                     // standing in front of group 0: a rotation by d groups brings group g - d to
                     // group g, and the carried sum (held by the last group) to group d - 1.
@@ -556,9 +584,20 @@ template <typename V, int LPR> __global__ __launch_bounds__(256) void bwd_reduce
                     }
                     if (g == G - 1 && dist_u >= G)
                         bwd_vec<V>::add(vg, cv); // the last group reaches back past group 0
+                    float step = a.lr;
+                    if (a.adagrad) { // one accumulator per row: grows by the row's mean squared gradient
+                        float q = bwd_vec<V>::sumsq(vg);
+#pragma unroll
+                        for (int m = 1; m < LPR; m <<= 1)
+                            q += __shfl_xor(q, m, FAE_WAVE);
+                        const float acc = sw[u] + q / (float)a.dim;
+                        step = a.lr / (sqrtf(acc) + a.eps);
+                        if (dest == 1 && l == 0)
+                            a.opt_state[sp.z][kg] = acc;
+                    }
                     if (active) {
                         if (dest == 1)
-                            W[(int64_t)kg * ncols + c] = bwd_vec<V>::sgd(ww[u], vg, a.lr);
+                            W[(int64_t)kg * ncols + c] = bwd_vec<V>::sgd(ww[u], vg, step);
                         else if (dest == 2)
                             part[c] = vg;
                         else if (dest == 3)
@@ -803,10 +842,23 @@ template <typename V, int LPR> __global__ __launch_bounds__(256) void bwd_fixup_
             const V o = bwd_shfl<V>(acc, lane ^ mm);
             bwd_vec<V>::add(acc, o);
         }
-        if (g == 0 && c < ncols) {
+        if (g == 0 && c < ncols)
             bwd_vec<V>::add(acc, tail);
-            *wp = bwd_vec<V>::sgd(wv, acc, a.lr);
+        float step = a.lr;
+        if (a.adagrad) { // group 0 holds the row's whole gradient; lanes past the row hold zeros
+            float q = c < ncols ? bwd_vec<V>::sumsq(acc) : 0.f;
+#pragma unroll
+            for (int mm = 1; mm < LPR; mm <<= 1)
+                q += __shfl_xor(q, mm, FAE_WAVE);
+            if (g == 0) {
+                const float nacc = a.opt_state[sp.z][k] + q / (float)a.dim;
+                step = a.lr / (sqrtf(nacc) + a.eps);
+                if (l == 0)
+                    a.opt_state[sp.z][k] = nacc;
+            }
         }
+        if (g == 0 && c < ncols)
+            *wp = bwd_vec<V>::sgd(wv, acc, step);
     }
 }
 
@@ -949,7 +1001,7 @@ template <typename V, int LPR> void launch_reduce(fae_ctx *ctx, const BwdArgs &a
     {
         fae_ktimer kt(ctx, FAE_K_BWD_REDUCE);
         const dim3 grid((a.n_spans + 3) / 4);
-        if (ctx->opt_reduce != 2)
+        if (ctx->opt_reduce != 2 || a.mean || a.adagrad) // the variants exist in the scan form only
             hipLaunchKernelGGL((bwd_reduce_kernel<V, LPR>), grid, dim3(256), 0, ctx->stream, a);
         else if (ctx->opt_unroll == 8)
             hipLaunchKernelGGL((bwd_reduce_walk_kernel<V, LPR, 8>), grid, dim3(256), 0, ctx->stream, a);
@@ -1340,10 +1392,46 @@ extern "C" int32_t fae_embbag_fwd_presort(fae_ctx *ctx, const fae_tables *hot_ta
     return FAE_OK;
 }
 
+static int32_t bwd_impl(fae_ctx *ctx, const fae_tables *hot_tables, float *const *h_hotW,
+                        const fae_batch *hot_batch, const float *gout, int64_t gout_row_stride,
+                        const fae_step_opts &opts, const fae_bwd_debug *dbg, void *ws, size_t ws_bytes);
+
 extern "C" int32_t fae_embbag_bwd_sgd(fae_ctx *ctx, const fae_tables *hot_tables, float *const *h_hotW,
                                       const fae_batch *hot_batch, const float *gout, int64_t gout_row_stride,
                                       float lr, const fae_bwd_debug *dbg, void *ws, size_t ws_bytes)
 {
+    fae_step_opts o;
+    memset(&o, 0, sizeof(o));
+    o.pooling = FAE_POOL_SUM;
+    o.optimizer = FAE_OPT_SGD;
+    o.lr = lr;
+    return bwd_impl(ctx, hot_tables, h_hotW, hot_batch, gout, gout_row_stride, o, dbg, ws, ws_bytes);
+}
+
+extern "C" int32_t fae_embbag_bwd_opts(fae_ctx *ctx, const fae_tables *hot_tables, float *const *h_hotW,
+                                       const fae_batch *hot_batch, const float *gout, int64_t gout_row_stride,
+                                       const fae_step_opts *opts, const fae_bwd_debug *dbg, void *ws,
+                                       size_t ws_bytes)
+{
+    if (!ctx)
+        return FAE_EINVAL;
+    if (!opts || (opts->pooling != FAE_POOL_SUM && opts->pooling != FAE_POOL_MEAN) ||
+        (opts->optimizer != FAE_OPT_SGD && opts->optimizer != FAE_OPT_ROWWISE_ADAGRAD))
+        return fae_fail(ctx, FAE_EINVAL, "fae_embbag_bwd_opts: null options, unknown pooling or unknown optimizer");
+    if (opts->optimizer == FAE_OPT_ROWWISE_ADAGRAD) {
+        if (!opts->h_state || !(opts->eps >= 0.f))
+            return fae_fail(ctx, FAE_EINVAL, "fae_embbag_bwd_opts: Adagrad needs accumulators and eps >= 0");
+        if (hot_tables && (hot_tables->dim > 256 || (hot_tables->dim % 4 != 0 && hot_tables->dim > 64)))
+            return fae_fail(ctx, FAE_EINVAL, "fae_embbag_bwd_opts: Adagrad needs dim <= 256 (<= 64 if dim %% 4 != 0)");
+    }
+    return bwd_impl(ctx, hot_tables, h_hotW, hot_batch, gout, gout_row_stride, *opts, dbg, ws, ws_bytes);
+}
+
+static int32_t bwd_impl(fae_ctx *ctx, const fae_tables *hot_tables, float *const *h_hotW,
+                        const fae_batch *hot_batch, const float *gout, int64_t gout_row_stride,
+                        const fae_step_opts &opts, const fae_bwd_debug *dbg, void *ws, size_t ws_bytes)
+{
+    const float lr = opts.lr;
     if (dbg && !dbg->table_start)
         return fae_fail(ctx, FAE_EINVAL, "fae_embbag_bwd_sgd: incomplete debug outputs");
     BwdSetup su;
@@ -1380,6 +1468,18 @@ extern "C" int32_t fae_embbag_bwd_sgd(fae_ctx *ctx, const fae_tables *hot_tables
     a.gout_stride = gout_row_stride;
     a.lr = lr;
     a.span = span;
+    a.mean = opts.pooling == FAE_POOL_MEAN;
+    a.adagrad = opts.optimizer == FAE_OPT_ROWWISE_ADAGRAD;
+    a.eps = opts.eps;
+    if (a.adagrad) {
+        for (int z = 0; z < nt; ++z) {
+            if (!opts.h_state[z] && hot_tables->h_rows[z] > 0)
+                return fae_fail(ctx, FAE_EINVAL, "fae_embbag_bwd_opts: null accumulators for table %d", z);
+            a.opt_state[z] = opts.h_state[z];
+        }
+        if (!vec && dim > 64) // the unaligned path has one column per lane
+            return fae_fail(ctx, FAE_EINVAL, "fae_embbag_bwd_opts: Adagrad on unaligned buffers needs dim <= 64");
+    }
 
     // 1 + 2. sorted (slot, sample) pairs: take them from a matching presort, or sort now
     int cur = 0;

@@ -20,6 +20,13 @@ template <> struct vec_ops<float4> {
         a.z += b.z;
         a.w += b.w;
     }
+    static __device__ __forceinline__ void scale(float4 &a, float f)
+    {
+        a.x *= f;
+        a.y *= f;
+        a.z *= f;
+        a.w *= f;
+    }
     static __device__ __forceinline__ float4 shfl_xor(const float4 &a, int m)
     {
         return make_float4(__shfl_xor(a.x, m, FAE_WAVE), __shfl_xor(a.y, m, FAE_WAVE),
@@ -29,6 +36,7 @@ template <> struct vec_ops<float4> {
 template <> struct vec_ops<float> {
     static __device__ __forceinline__ float zero() { return 0.f; }
     static __device__ __forceinline__ void add(float &a, const float &b) { a += b; }
+    static __device__ __forceinline__ void scale(float &a, float f) { a *= f; }
     static __device__ __forceinline__ float shfl_xor(const float &a, int m) { return __shfl_xor(a, m, FAE_WAVE); }
 };
 

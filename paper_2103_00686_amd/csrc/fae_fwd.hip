@@ -25,6 +25,7 @@ struct FwdArgs {
     float *out;
     uint32_t *status;
     int32_t stream_out; // non-temporal stores for the pooled output
+    int32_t mean;       // divide the pooled sum by the bag's length (bags of one lookup are unaffected)
 };
 
 // one row slice, or zero (and a status flag) when the slot is out of range
@@ -77,6 +78,8 @@ template <typename V, int LPR> __global__ __launch_bounds__(256) void fwd_group_
             V v = fwd_load(W, slots[j], n_hot, ncols, c, a.status);
             vec_ops<V>::add(acc, v);
         }
+        if (a.mean && end - beg > 1)
+            vec_ops<V>::scale(acc, 1.0f / (float)(end - beg));
         o[c] = acc;
     }
 }
@@ -139,6 +142,8 @@ template <typename V, int LPR> __global__ __launch_bounds__(256) void fwd_wave_k
 #pragma unroll
         for (int m = LPR; m < FAE_WAVE; m <<= 1)
             vec_ops<V>::add(acc, vec_ops<V>::shfl_xor(acc, m));
+        if (a.mean && end - beg > 1)
+            vec_ops<V>::scale(acc, 1.0f / (float)(end - beg));
         if (g == 0 && c < ncols)
             o[c] = acc;
     }
@@ -167,8 +172,28 @@ template <typename V> static void fwd_dispatch(fae_ctx *ctx, const FwdArgs &a, i
     }
 }
 
+static int32_t fwd_impl(fae_ctx *ctx, const fae_tables *hot_tables, const float *const *h_hotW,
+                        const fae_batch *hot_batch, float *out, int64_t out_row_stride, int pooling);
+
 extern "C" int32_t fae_embbag_fwd(fae_ctx *ctx, const fae_tables *hot_tables, const float *const *h_hotW,
                                   const fae_batch *hot_batch, float *out, int64_t out_row_stride)
+{
+    return fwd_impl(ctx, hot_tables, h_hotW, hot_batch, out, out_row_stride, FAE_POOL_SUM);
+}
+
+extern "C" int32_t fae_embbag_fwd_opts(fae_ctx *ctx, const fae_tables *hot_tables, const float *const *h_hotW,
+                                       const fae_batch *hot_batch, float *out, int64_t out_row_stride,
+                                       const fae_step_opts *opts)
+{
+    if (!ctx)
+        return FAE_EINVAL;
+    if (!opts || (opts->pooling != FAE_POOL_SUM && opts->pooling != FAE_POOL_MEAN))
+        return fae_fail(ctx, FAE_EINVAL, "fae_embbag_fwd_opts: null options or unknown pooling");
+    return fwd_impl(ctx, hot_tables, h_hotW, hot_batch, out, out_row_stride, opts->pooling);
+}
+
+static int32_t fwd_impl(fae_ctx *ctx, const fae_tables *hot_tables, const float *const *h_hotW,
+                        const fae_batch *hot_batch, float *out, int64_t out_row_stride, int pooling)
 {
     int32_t rc = fae_check_tables(ctx, hot_tables, "fae_embbag_fwd");
     if (rc != FAE_OK)
@@ -210,6 +235,7 @@ extern "C" int32_t fae_embbag_fwd(fae_ctx *ctx, const fae_tables *hot_tables, co
     a.out = out;
     a.status = ctx->d_block;
     a.stream_out = ctx->opt_fwd_stream != 0;
+    a.mean = pooling == FAE_POOL_MEAN;
     // one-hot tables: 256 samples per workgroup
     if (ctx->opt_fwd == 0) {
         const int64_t per_table = (S + 255) / 256;

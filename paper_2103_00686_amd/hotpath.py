@@ -173,10 +173,13 @@ class HotPath:
         return hot[:n_hot], cold[:S - n_hot], hb
 
     # -- a6 -------------------------------------------------------------------------
-    def forward(self, hb: HotBatch, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    def forward(self, hb: HotBatch, out: Optional[torch.Tensor] = None, pooling: int = B.FAE_POOL_SUM) -> torch.Tensor:
         if out is None:
             out = torch.empty((hb.n_samples, self.nt, self.dim), dtype=torch.float32, device=self.dev)
-        B.fae_embbag_fwd(self.ctx, self.hot_tables, self.hotW, hb.batch(), out, self.nt * self.dim)
+        if pooling == B.FAE_POOL_SUM:
+            B.fae_embbag_fwd(self.ctx, self.hot_tables, self.hotW, hb.batch(), out, self.nt * self.dim)
+        else:
+            B.fae_embbag_fwd_opts(self.ctx, self.hot_tables, self.hotW, hb.batch(), out, self.nt * self.dim, pooling)
         return out
 
     # -- a7 + a8 --------------------------------------------------------------------
@@ -204,6 +207,20 @@ class HotPath:
         tstart = torch.zeros(self.nt + 1, dtype=torch.int32, device=self.dev)
         B.fae_embbag_bwd_sgd(self.ctx, self.hot_tables, self.hotW, hb.batch(), gout, self.nt * self.dim, lr, ws,
                              uniq, runlen, tstart)
+        ts = tstart.cpu().tolist()
+        return ([uniq[ts[z]:ts[z + 1]] for z in range(self.nt)], [runlen[ts[z]:ts[z + 1]] for z in range(self.nt)])
+
+    def backward_opts(self, hb: HotBatch, gout: torch.Tensor, lr: float, pooling: int = B.FAE_POOL_SUM,
+                      optimizer: int = B.FAE_OPT_SGD, eps: float = 0.0, state: Optional[List[torch.Tensor]] = None):
+        """Backward with a pooling / optimizer variant; returns the distinct slots and their
+        multiplicities per table like ``backward_sgd(debug=True)``."""
+        ws = self.bwd_workspace(hb)
+        n = max(sum(hb.n_lookups), 1)
+        uniq = torch.empty(n, dtype=torch.int32, device=self.dev)
+        runlen = torch.empty(n, dtype=torch.int32, device=self.dev)
+        tstart = torch.zeros(self.nt + 1, dtype=torch.int32, device=self.dev)
+        B.fae_embbag_bwd_opts(self.ctx, self.hot_tables, self.hotW, hb.batch(), gout, self.nt * self.dim, lr, ws,
+                              pooling, optimizer, eps, state, uniq, runlen, tstart)
         ts = tstart.cpu().tolist()
         return ([uniq[ts[z]:ts[z + 1]] for z in range(self.nt)], [runlen[ts[z]:ts[z + 1]] for z in range(self.nt)])
 

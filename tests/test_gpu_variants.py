@@ -1,0 +1,156 @@
+"""GPU parity of the pooling and optimizer variants (mean pooling, row-wise Adagrad): the
+paper names the pooled lookup and the optimizer step (Sec. 2.2) without fixing either.
+
+Tolerances.  Forward and SGD update: |gpu - ref| <= 1e-5 * sum|terms| as for the plain path.
+Adagrad: with G the row's summed gradient, gamma = 1e-5 * sum|g| the bound on its error,
+a = accumulator + mean(G^2) and scale = lr / (sqrt(a) + eps), first-order propagation gives
+  |a' - a|   <= mean(2|G| gamma + gamma^2) + 2^-22 a                     =: da
+  |w' - w|   <= scale * gamma + |G| * scale * da / (2 sqrt(a) (sqrt(a) + eps)) + 1e-6 (|w| + scale |G|)
+and the test allows twice that.  Rows and accumulators the step does not touch are bit-identical;
+a later step inherits the bound of the earlier one (added to both)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import fae_oracle as O
+from paper_2103_00686_amd import binding as B
+from paper_2103_00686_amd.hotpath import HotBatch, HotPath
+
+import fae_testlib as T
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def dev():
+    return torch.device("cuda", 0)
+
+
+def _batch(rng, n_hot, S_, dev):
+    """Three tables: ragged bags 0..40 with empties and repeats, one-hot, long bags."""
+    slots, offs = [], []
+    for z, n in enumerate(n_hot):
+        if z == 1:
+            slots.append(rng.integers(0, n, S_).astype(np.int32))
+            offs.append(None)
+            continue
+        lens = rng.integers(0, 41, S_) if z == 0 else rng.integers(30, 120, S_)
+        if z == 0:
+            lens[rng.integers(0, S_, S_ // 8)] = 0
+        o = np.zeros(S_ + 1, dtype=np.int32)
+        o[1:] = np.cumsum(lens)
+        s = rng.integers(0, n, int(o[-1])).astype(np.int32)
+        s[: s.size // 3] = rng.integers(0, min(n, 5), s.size // 3)      # a few very frequent rows: runs that cross spans
+        slots.append(rng.permutation(s))
+        offs.append(o)
+    hb = HotBatch(S_, [torch.from_numpy(s).to(dev) for s in slots],
+                  [None if o is None else torch.from_numpy(o).to(dev) for o in offs], [s.size for s in slots])
+    return hb, slots, offs
+
+
+@pytest.mark.parametrize("dim", [64, 20, 128, 4, 256])
+def test_mean_forward(dev, dim):
+    rng = np.random.default_rng(200 + dim)
+    n_hot, S_ = [900, 50, 3000], 700
+    hp = HotPath(n_hot, dim, 0)
+    hp.n_hot = n_hot
+    Wref = [(rng.random((n, dim), dtype=np.float32) - 0.5) for n in n_hot]
+    hp.hotW = [torch.from_numpy(x).to(dev) for x in Wref]
+    hb, slots, offs = _batch(rng, n_hot, S_, dev)
+    for fwd_variant in (0, 1, 2):
+        B.fae_set_option(hp.ctx, "fwd_variant", fwd_variant)
+        out = hp.forward(hb, pooling=B.FAE_POOL_MEAN).cpu().numpy()
+        ref, mag = O.embbag_fwd_mean(Wref, S_, slots, offs, want_mag=True)
+        T.assert_close_sum(out, ref, mag, f"mean forward (variant {fwd_variant})")
+        empty = np.diff(offs[0]) == 0
+        assert not out[empty, 0, :].any()
+        assert out[:, 1, :].tobytes() == ref[:, 1, :].tobytes()          # bags of one lookup: a copy
+
+
+def _adagrad_bound(G, Ga, w_old, st_old, lr, eps, dim):
+    gamma = 1e-5 * Ga
+    a = st_old.astype(np.float64) + (G * G).mean(axis=1)
+    da = (2 * np.abs(G) * gamma + gamma * gamma).mean(axis=1) + 2.0 ** -22 * a
+    sq = np.sqrt(a)
+    scale = lr / (sq + eps)
+    dscale = scale * da / np.maximum(2 * sq * (sq + eps), 1e-300)
+    bw = scale[:, None] * gamma + np.abs(G) * dscale[:, None] + 1e-6 * (np.abs(w_old) + scale[:, None] * np.abs(G))
+    return 2 * bw, 2 * da
+
+
+@pytest.mark.parametrize("dim", [64, 20, 128, 4])
+@pytest.mark.parametrize("pooling,optimizer", [(B.FAE_POOL_MEAN, B.FAE_OPT_SGD), (B.FAE_POOL_SUM, B.FAE_OPT_ROWWISE_ADAGRAD),
+                                               (B.FAE_POOL_MEAN, B.FAE_OPT_ROWWISE_ADAGRAD)])
+def test_backward_variants(dev, dim, pooling, optimizer):
+    rng = np.random.default_rng(300 + dim + 7 * pooling + 13 * optimizer)
+    n_hot, S_, lr, eps = [900, 50, 3000], 700, 0.05, 1e-3
+    hp = HotPath(n_hot, dim, 0)
+    hp.n_hot = n_hot
+    Wref = [(rng.random((n, dim), dtype=np.float32) - 0.5) for n in n_hot]
+    Sref = [np.zeros(n, np.float32) for n in n_hot]
+    hp.hotW = [torch.from_numpy(x.copy()).to(dev) for x in Wref]
+    state = [torch.zeros(n, dtype=torch.float32, device=dev) for n in n_hot]
+    wtol = [np.zeros((n, dim)) for n in n_hot]
+    stol = [np.zeros(n) for n in n_hot]
+    for step in range(2):
+        hb, slots, offs = _batch(rng, n_hot, S_, dev)
+        gout = rng.standard_normal((S_, 3, dim)).astype(np.float32)
+        w_before = [x.clone() for x in hp.hotW]
+        s_before = [x.clone() for x in state]
+        dbg = hp.backward_opts(hb, torch.from_numpy(gout).to(dev), lr, pooling, optimizer, eps,
+                               state if optimizer == B.FAE_OPT_ROWWISE_ADAGRAD else None)
+        hp.sync()
+        res = O.embbag_bwd_opts(Wref, Sref, S_, slots, offs, gout, lr, eps, pooling, optimizer)
+        for z in range(3):
+            uniq, runlen, G, Ga, w_old, st_old = res[z]
+            assert np.array_equal(dbg[0][z].cpu().numpy(), uniq) and np.array_equal(dbg[1][z].cpu().numpy(), runlen)
+            got = hp.hotW[z].cpu().numpy()
+            cold = np.ones(n_hot[z], bool)
+            cold[uniq] = False
+            assert got[cold].tobytes() == w_before[z].cpu().numpy()[cold].tobytes(), f"untouched rows of table {z} changed"
+            if optimizer == B.FAE_OPT_ROWWISE_ADAGRAD:
+                gs = state[z].cpu().numpy()
+                assert gs[cold].tobytes() == s_before[z].cpu().numpy()[cold].tobytes()
+                bw, bs = _adagrad_bound(G, Ga, w_old, st_old, lr, eps, dim)
+                bw += wtol[z][uniq] * (1 + 1e-3)
+                bs += stol[z][uniq] * (1 + 1e-3)
+                assert (np.abs(gs[uniq].astype(np.float64) - Sref[z][uniq]) <= bs + 1e-30).all(), f"accumulators of table {z}"
+                stol[z][uniq] = bs
+            else:
+                bw = 1e-5 * (np.abs(w_old) + lr * Ga) + wtol[z][uniq] * (1 + 1e-3)
+            err = np.abs(got[uniq].astype(np.float64) - Wref[z][uniq])
+            assert (err <= bw + 1e-30).all(), f"rows of table {z}: worst ratio {float((err / (bw + 1e-30)).max()):.3g}"
+            wtol[z][uniq] = bw
+
+
+def test_variants_integer_case_is_bit_exact_and_arguments(dev):
+    """Mean pooling over bags whose lengths are powers of two, integer weights and gradients,
+    lr a power of two: every operation is exact, so both sides agree bit for bit."""
+    rng = np.random.default_rng(77)
+    dim, n_hot, S_ = 16, 120, 500
+    lens = 2 ** rng.integers(0, 4, S_)
+    o = np.zeros(S_ + 1, dtype=np.int32)
+    o[1:] = np.cumsum(lens)
+    slots = rng.integers(0, n_hot, int(o[-1])).astype(np.int32)
+    W = (8 * rng.integers(-8, 9, (n_hot, dim))).astype(np.float32)
+    hp = HotPath([n_hot], dim, 0)
+    hp.n_hot = [n_hot]
+    hp.hotW = [torch.from_numpy(W.copy()).to(dev)]
+    hb = HotBatch(S_, [torch.from_numpy(slots).to(dev)], [torch.from_numpy(o).to(dev)], [slots.size])
+    out = hp.forward(hb, pooling=B.FAE_POOL_MEAN).cpu().numpy()
+    assert out.tobytes() == O.embbag_fwd_mean([W], S_, [slots], [o]).tobytes()
+    gout = (8 * rng.integers(-4, 5, (S_, 1, dim))).astype(np.float32)
+    hp.backward_opts(hb, torch.from_numpy(gout).to(dev), 0.25, B.FAE_POOL_MEAN)
+    hp.sync()
+    Wr = [W.copy()]
+    O.embbag_bwd_opts(Wr, None, S_, [slots], [o], gout, 0.25, 0.0, O.POOL_MEAN)
+    assert hp.hotW[0].cpu().numpy().tobytes() == Wr[0].tobytes()
+    # bad arguments
+    ws = hp.bwd_workspace(hb)
+    with pytest.raises(B.FaeError):
+        B.fae_embbag_bwd_opts(hp.ctx, hp.hot_tables, hp.hotW, hb.batch(), torch.from_numpy(gout).to(dev), dim, 0.1, ws, pooling=5)
+    with pytest.raises(B.FaeError):
+        B.fae_embbag_bwd_opts(hp.ctx, hp.hot_tables, hp.hotW, hb.batch(), torch.from_numpy(gout).to(dev), dim, 0.1, ws,
+                              optimizer=B.FAE_OPT_ROWWISE_ADAGRAD, state=None)
+    with pytest.raises(B.FaeError):
+        B.fae_embbag_fwd_opts(hp.ctx, hp.hot_tables, hp.hotW, hb.batch(), torch.empty((S_, 1, dim), device=dev), dim, 9)
