@@ -65,6 +65,11 @@ typedef struct {
     const int32_t *const *h_indices; /* host [n_tables] -> device int32[n_lookups_z]  */
     const int32_t *const *h_offsets; /* host [n_tables] -> device int32[n_samples+1]  */
     const int64_t *h_n_lookups;      /* host [n_tables]                               */
+    /* 0 or 32: the indices are int32.  64: they are int64 (h_indices[z] then points at
+     * device int64[n_lookups_z]); accepted by fae_profile and fae_partition_batch, whose
+     * inputs are raw row ids; values outside [0, rows_z) are reported as FAE_ERANGE as
+     * usual.  Hot sub-batches (hot slots) are always int32. */
+    int32_t index_bits;
 } fae_batch;
 
 /* Where fae_build_hot_tables takes the weights of hot rows from. */

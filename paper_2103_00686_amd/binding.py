@@ -48,7 +48,8 @@ class _Tables(C.Structure):
 
 class _Batch(C.Structure):
     _fields_ = [("n_samples", C.c_int64), ("h_indices", C.POINTER(C.c_void_p)),
-                ("h_offsets", C.POINTER(C.c_void_p)), ("h_n_lookups", C.POINTER(C.c_int64))]
+                ("h_offsets", C.POINTER(C.c_void_p)), ("h_n_lookups", C.POINTER(C.c_int64)),
+                ("index_bits", C.c_int32)]
 
 
 class _WeightSrc(C.Structure):
@@ -129,18 +130,19 @@ class Tables:
 @dataclass
 class Batch:
     n_samples: int
-    indices: List[torch.Tensor]                 # per table, device int32
+    indices: List[torch.Tensor]                 # per table, device int32 (or int64 with index_bits=64)
     offsets: List[Optional[torch.Tensor]]       # per table, device int32[S+1] or None
     n_lookups: Sequence[int]
+    index_bits: int = 32
 
     def c(self):
         """Marshalled once per Batch object (the tensors must stay alive and in place)."""
         if getattr(self, "_c", None) is None:
             nt = len(self.indices)
-            idx = _ptrs(self.indices, torch.int32)
+            idx = _ptrs(self.indices, torch.int64 if self.index_bits == 64 else torch.int32)
             off = _ptrs(self.offsets, torch.int32) if any(o is not None for o in self.offsets) else None
             nl = (C.c_int64 * nt)(*[int(n) for n in self.n_lookups])
-            b = _Batch(int(self.n_samples), idx, off, nl)
+            b = _Batch(int(self.n_samples), idx, off, nl, int(self.index_bits))
             b._keep = (idx, off, nl)
             self._c = b
         return self._c

@@ -1053,6 +1053,8 @@ int32_t bwd_setup(fae_ctx *ctx, const fae_tables *hot_tables, const fae_batch *h
     rc = fae_check_batch(ctx, hot_tables, hot_batch, who);
     if (rc != FAE_OK)
         return rc;
+    if (hot_batch->index_bits == 64)
+        return fae_fail(ctx, FAE_EINVAL, "%s: hot slots are int32", who);
     const int nt = hot_tables->n_tables, dim = hot_tables->dim;
     out->plan = bwd_plan(nt, hot_batch->h_n_lookups);
     if (out->plan.N >= 2147483647LL - SORT_TILE)

@@ -285,6 +285,8 @@ int32_t fae_check_batch(fae_ctx *ctx, const fae_tables *t, const fae_batch *b, c
         return fae_fail(ctx, FAE_EINVAL, "%s: null batch", who);
     if (b->n_samples < 0 || b->n_samples >= 2147483647LL)
         return fae_fail(ctx, FAE_EINVAL, "%s: n_samples=%lld outside [0,2^31-1)", who, (long long)b->n_samples);
+    if (b->index_bits != 0 && b->index_bits != 32 && b->index_bits != 64)
+        return fae_fail(ctx, FAE_EINVAL, "%s: index_bits=%d is neither 32 nor 64", who, b->index_bits);
     for (int z = 0; z < t->n_tables; ++z) {
         int64_t nl = b->h_n_lookups[z];
         if (nl < 0 || nl >= 2147483647LL)

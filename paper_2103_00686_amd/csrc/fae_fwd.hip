@@ -201,6 +201,8 @@ static int32_t fwd_impl(fae_ctx *ctx, const fae_tables *hot_tables, const float 
     rc = fae_check_batch(ctx, hot_tables, hot_batch, "fae_embbag_fwd");
     if (rc != FAE_OK)
         return rc;
+    if (hot_batch->index_bits == 64)
+        return fae_fail(ctx, FAE_EINVAL, "fae_embbag_fwd: hot slots are int32");
     const int nt = hot_tables->n_tables, dim = hot_tables->dim;
     const int64_t S = hot_batch->n_samples;
     if (S == 0)

@@ -140,6 +140,17 @@ __device__ __forceinline__ int fae_find_table(const int32_t *blk_start, int nt, 
     return z;
 }
 
+// raw row id j of an index array that holds int32 or int64 values; -1 if it is outside [0, rows)
+__device__ __forceinline__ int fae_load_row(const void *idx, int64_t j, int wide, int rows)
+{
+    if (wide) {
+        const int64_t v = ((const int64_t *)idx)[j];
+        return (v >= 0 && v < (int64_t)rows) ? (int)v : -1;
+    }
+    const int v = ((const int32_t *)idx)[j];
+    return (unsigned)v < (unsigned)rows ? v : -1;
+}
+
 // inclusive scan across the 64 lanes of a wave
 __device__ __forceinline__ int fae_wave_incl_scan(int v)
 {

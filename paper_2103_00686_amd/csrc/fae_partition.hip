@@ -8,7 +8,8 @@
 #define PT_TILE 1024 // samples per scan tile (4 per thread)
 
 struct PartArgs {
-    const int32_t *idx[FAE_MAX_TABLES];
+    const void *idx[FAE_MAX_TABLES]; // int32 or int64 row ids
+    int32_t wide;                    // the ids are int64
     const int32_t *offsets[FAE_MAX_TABLES];
     const int32_t *remap[FAE_MAX_TABLES];
     int32_t *slots[FAE_MAX_TABLES];
@@ -37,8 +38,8 @@ __global__ __launch_bounds__(256) void part_mark_kernel(PartArgs a)
         return;
     const int32_t *off = a.offsets[z];
     const int s = off ? fae_sample_of(off, a.n_samples, j) : j;
-    const int r = a.idx[z][j];
-    if ((unsigned)r >= (unsigned)a.n_rows[z]) {
+    const int r = fae_load_row(a.idx[z], j, a.wide, a.n_rows[z]);
+    if (r < 0) {
         fae_flag(a.status, FAE_STATUS_ERANGE);
         a.cold[s] = 1u;
         return;
@@ -174,7 +175,9 @@ __global__ __launch_bounds__(256) void part_slots_kernel(PartArgs a)
     const int dst = a.hoffsets[z][h] + within;
     if (within < 0 || dst < 0 || dst >= a.n_lookups[z])
         return; // malformed CSR (already flagged)
-    a.slots[z][dst] = a.remap[z][a.idx[z][j]]; // hot sample: every index was validated in pass 1
+    const int r = fae_load_row(a.idx[z], j, a.wide, a.n_rows[z]);
+    if (r >= 0) // always, for a hot sample: every index was validated in pass 1
+        a.slots[z][dst] = a.remap[z][r];
 }
 
 static int64_t part_tiles(int64_t S) { return (S + PT_TILE - 1) / PT_TILE; }
@@ -234,6 +237,7 @@ extern "C" int32_t fae_partition_batch(fae_ctx *ctx, const fae_tables *tables, c
         if (!h_hoffsets[z] || (!h_slots[z] && in->h_n_lookups[z] > 0))
             return fae_fail(ctx, FAE_EINVAL, "fae_partition_batch: null outputs for table %d", z);
         a.idx[z] = in->h_indices[z];
+        a.wide = in->index_bits == 64;
         a.offsets[z] = in->h_offsets ? in->h_offsets[z] : nullptr;
         a.remap[z] = h_remap[z];
         a.slots[z] = h_slots[z];

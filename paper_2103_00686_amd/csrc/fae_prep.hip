@@ -11,7 +11,8 @@
 // a1  Embedding Logger: counts_z[r] += #lookups of r        (Sec. 4.1.2)
 // =================================================================================
 struct ProfArgs {
-    const int32_t *idx[FAE_MAX_TABLES];
+    const void *idx[FAE_MAX_TABLES]; // int32 or int64 row ids
+    int32_t wide;                    // the ids are int64
     uint32_t *cnt[FAE_MAX_TABLES];
     int32_t n_rows[FAE_MAX_TABLES];
     int32_t n_lookups[FAE_MAX_TABLES];
@@ -26,15 +27,15 @@ __global__ __launch_bounds__(256) void prof_atomic_kernel(ProfArgs a)
 {
     const int z = fae_find_table(a.blk_start, a.n_tables, blockIdx.x);
     const int bl = blockIdx.x - a.blk_start[z];
-    const int32_t *idx = a.idx[z];
+    const void *idx = a.idx[z];
     uint32_t *cnt = a.cnt[z];
     const int n = a.n_lookups[z], R = a.n_rows[z];
     const int64_t beg = (int64_t)bl * a.span;
     const int64_t end = beg + a.span < n ? beg + a.span : n;
     bool bad = false;
     for (int64_t j = beg + threadIdx.x; j < end; j += 256) {
-        int r = idx[j];
-        if ((unsigned)r < (unsigned)R)
+        const int r = fae_load_row(idx, j, a.wide, R);
+        if (r >= 0)
             atomicAdd(&cnt[r], 1u);
         else
             bad = true;
@@ -58,7 +59,7 @@ __global__ __launch_bounds__(PROF_THREADS) void prof_lds_kernel(ProfArgs a)
     __shared__ uint32_t lds[PROF_DENSE_MAX]; // dense counters, or [keys | counts] of the hash
     const int z = fae_find_table(a.blk_start, a.n_tables, blockIdx.x);
     const int bl = blockIdx.x - a.blk_start[z];
-    const int32_t *idx = a.idx[z];
+    const void *idx = a.idx[z];
     uint32_t *cnt = a.cnt[z];
     const int n = a.n_lookups[z], R = a.n_rows[z];
     const int64_t beg = (int64_t)bl * a.span;
@@ -69,8 +70,8 @@ __global__ __launch_bounds__(PROF_THREADS) void prof_lds_kernel(ProfArgs a)
             lds[i] = 0u;
         __syncthreads();
         for (int64_t j = beg + threadIdx.x; j < end; j += PROF_THREADS) {
-            int r = idx[j];
-            if ((unsigned)r < (unsigned)R)
+            const int r = fae_load_row(idx, j, a.wide, R);
+            if (r >= 0)
                 atomicAdd(&lds[r], 1u);
             else
                 bad = true;
@@ -90,8 +91,8 @@ __global__ __launch_bounds__(PROF_THREADS) void prof_lds_kernel(ProfArgs a)
         }
         __syncthreads();
         for (int64_t j = beg + threadIdx.x; j < end; j += PROF_THREADS) {
-            int r = idx[j];
-            if ((unsigned)r >= (unsigned)R) {
+            const int r = fae_load_row(idx, j, a.wide, R);
+            if (r < 0) {
                 bad = true;
                 continue;
             }
@@ -154,6 +155,7 @@ extern "C" int32_t fae_profile(fae_ctx *ctx, const fae_tables *tables, const fae
         if (!h_counts[z] && tables->h_rows[z] > 0)
             return fae_fail(ctx, FAE_EINVAL, "fae_profile: null counters for table %d", z);
         a.idx[z] = chunk->h_indices[z];
+        a.wide = chunk->index_bits == 64;
         a.cnt[z] = h_counts[z];
         a.n_rows[z] = (int32_t)tables->h_rows[z];
         a.n_lookups[z] = (int32_t)chunk->h_n_lookups[z];

@@ -266,3 +266,46 @@ def test_errors_are_reported_not_fatal(dev):
         B.fae_embbag_bwd_sgd(hp.ctx, hp.hot_tables, hp.hotW, HotBatch(3, [torch.zeros(3, dtype=torch.int32, device=dev)], [None], [3]).batch(),
                              torch.ones((3, 1, 8), device=dev), 8, 0.1, torch.empty(256, dtype=torch.uint8, device=dev))
     assert e.value.code == B.FAE_ENOSPC
+
+
+@pytest.mark.parametrize("cfg_id", [2, 4])
+def test_int64_row_ids(dev, cfg_id):
+    """Raw row ids as int64 (the usual dtype of index tensors): histogram and partition give
+    the results of the int32 path; ids outside the table (also beyond 2^31) are reported."""
+    w = S.workload(cfg_id, "test")
+    p = T.Pipeline(w, dev, profile_chunks=1)
+    for ch in p.prof:
+        b = B.Batch(ch.n_samples, [i.to(torch.int64).to(dev) for i in ch.indices],
+                    [None if o is None else o.to(dev) for o in ch.offsets], list(ch.n_lookups), index_bits=64)
+        p.hp.profile(b)
+    p.hp.sync()
+    p.cnts = T.oracle_profile(w, p.prof)
+    for z in range(w.n_tables):
+        assert np.array_equal(p.hp.counts[z][:w.rows[z]].cpu().numpy().view(np.uint32), p.cnts[z])
+    p.check_cutoff()
+    p.check_build()
+    mixed = S.make_chunk(w, 5, 0, 2 * w.batch + 19)
+    idx, off = T.np_idx(mixed)
+    hs, cs, slots, hoff = O.partition(w.rows, mixed.n_samples, idx, off, p.remap)
+    b = B.Batch(mixed.n_samples, [i.to(torch.int64).to(dev) for i in mixed.indices],
+                [None if o is None else o.to(dev) for o in mixed.offsets], list(mixed.n_lookups), index_bits=64)
+    ghs, gcs, hb = p.hp.partition(b)
+    assert np.array_equal(ghs.cpu().numpy(), hs) and np.array_equal(gcs.cpu().numpy(), cs)
+    for z in range(w.n_tables):
+        assert np.array_equal(hb.slots[z].cpu().numpy(), slots[z])
+    # an id beyond 2^31 and a negative one: never dereferenced, reported
+    bad = [i.to(torch.int64).clone() for i in mixed.indices]
+    bad[0][0] = (1 << 40) + 3
+    bad[0][1] = -5
+    bb = B.Batch(mixed.n_samples, [i.to(dev) for i in bad], [None if o is None else o.to(dev) for o in mixed.offsets],
+                 list(mixed.n_lookups), index_bits=64)
+    p.hp.profile(bb)
+    with pytest.raises(B.FaeError) as e:
+        p.hp.sync()
+    assert e.value.code == B.FAE_ERANGE
+    with pytest.raises(B.FaeError) as e:        # hot sub-batches are int32
+        hb64 = HotBatch(hb.n_samples, hb.slots, hb.offsets, hb.n_lookups)
+        bt = B.Batch(hb.n_samples, [s_.to(torch.int64) for s_ in hb.slots], hb.offsets, hb.n_lookups, index_bits=64)
+        B.fae_embbag_fwd(p.hp.ctx, p.hp.hot_tables, p.hp.hotW, bt,
+                         torch.empty((hb.n_samples, w.n_tables, w.dim), device=dev), w.n_tables * w.dim)
+    assert e.value.code == B.FAE_EINVAL
