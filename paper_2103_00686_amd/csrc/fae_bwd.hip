@@ -26,6 +26,10 @@
 #define SORT_ITEMS 16
 #define SORT_WAVES (SORT_THREADS / FAE_WAVE)
 #define SORT_TILE (SORT_THREADS * SORT_ITEMS)
+// short lists: smaller tiles, so that a chained pass has enough workgroups and a short chain per tile
+#define SORT_ITEMS_SMALL 4
+#define SORT_TILE_SMALL (SORT_THREADS * SORT_ITEMS_SMALL)
+#define SORT_SMALL_MAX_TILES 1024 // small tiles are used up to this many of them
 
 #define BWD_SPAN_MAX 256 // sorted lookups per wave in the reduce kernel (multiple of 64)
 #define BWD_SPAN_MIN 64
@@ -241,6 +245,7 @@ __global__ __launch_bounds__(256) void sort_colscan_kernel(BwdArgs a)
 // counters; the tile is then put in digit order inside LDS so that the global writes of a
 // digit are runs of consecutive addresses instead of single scattered words.
 //
+// ITEMS = keys per thread (a tile is 256 * ITEMS keys).
 // CHAINED = false: the tile's output offsets come from the histogram / column-scan kernels.
 // CHAINED = true : the whole pass is this one kernel.  Tiles are handed out in order by a
 // ticket counter; a tile publishes its digit counts, then adds up the published counts of
@@ -248,12 +253,13 @@ __global__ __launch_bounds__(256) void sort_colscan_kernel(BwdArgs a)
 // running total) and publishes its own running total.  A tile only ever waits for tiles
 // with smaller tickets, which are already running, so every wait ends; the wait is bounded
 // anyway and reports an internal error instead of spinning forever.
-template <bool CHAINED> __global__ __launch_bounds__(SORT_THREADS) void sort_scatter_kernel(BwdArgs a)
+template <bool CHAINED, int ITEMS> __global__ __launch_bounds__(SORT_THREADS) void sort_scatter_kernel(BwdArgs a)
 {
+    constexpr int TILE = SORT_THREADS * ITEMS;
     __shared__ int wcnt[SORT_WAVES][RADIX];  // per wave: running count, then start inside the tile
     __shared__ int gbase[RADIX];             // global position of the tile's first element of a digit
     __shared__ int tbase[RADIX];             // position inside the tile of the first element of a digit
-    __shared__ int skey[SORT_TILE], sval[SORT_TILE];
+    __shared__ int skey[TILE], sval[TILE];
     __shared__ int scan_lds[SORT_THREADS / FAE_WAVE + 1];
     __shared__ int s_tile;
     int tile = blockIdx.x;
@@ -268,26 +274,26 @@ template <bool CHAINED> __global__ __launch_bounds__(SORT_THREADS) void sort_sca
     const int tiles_z = a.tile_start[z + 1] - a.tile_start[z];
     const int seg1 = a.seg_start[z + 1];
     const int w = threadIdx.x / FAE_WAVE, lane = fae_lane();
-    const int tile0 = a.seg_start[z] + tl * SORT_TILE;
-    const int base = tile0 + w * (FAE_WAVE * SORT_ITEMS);
-    const int n_tile = seg1 - tile0 < SORT_TILE ? seg1 - tile0 : SORT_TILE;
+    const int tile0 = a.seg_start[z] + tl * TILE;
+    const int base = tile0 + w * (FAE_WAVE * ITEMS);
+    const int n_tile = seg1 - tile0 < TILE ? seg1 - tile0 : TILE;
     volatile int *my_cnt = wcnt[w];
 #pragma unroll
     for (int i = 0; i < RADIX / FAE_WAVE; ++i)
         my_cnt[i * FAE_WAVE + lane] = 0;
     __builtin_amdgcn_wave_barrier();
 
-    int key[SORT_ITEMS], val[SORT_ITEMS], off[SORT_ITEMS];
+    int key[ITEMS], val[ITEMS], off[ITEMS];
     const uint64_t lt_mask = (1ull << lane) - 1ull;
 #pragma unroll
-    for (int i = 0; i < SORT_ITEMS; ++i) {
+    for (int i = 0; i < ITEMS; ++i) {
         const int p = base + i * FAE_WAVE + lane;
         const bool valid = p < seg1;
         key[i] = valid ? a.keys_in[p] : 0;
         val[i] = valid ? a.vals_in[p] : 0;
     }
 #pragma unroll
-    for (int i = 0; i < SORT_ITEMS; ++i) {
+    for (int i = 0; i < ITEMS; ++i) {
         const bool valid = base + i * FAE_WAVE + lane < seg1;
         const int d = (key[i] >> a.shift) & a.mask;
         // lanes of this round that hold the same digit (valid lanes only)
@@ -326,23 +332,40 @@ template <bool CHAINED> __global__ __launch_bounds__(SORT_THREADS) void sort_sca
                 __hip_atomic_store(st, (SWEEP_PREFIX << 30) | mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             } else {
                 __hip_atomic_store(st, (SWEEP_AGGREGATE << 30) | mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                const uint32_t *look = st - RADIX;
+                // Walk back over the earlier tiles of the table, eight at a time (their words are
+                // loaded together; a tile that has published nothing yet is read again).  The
+                // table's first tile publishes a running total, so the walk stops there at the latest.
+                int back = 1; // distance of the nearest tile not yet added
                 int spins = 0;
-                for (;;) {
-                    const uint32_t v = __hip_atomic_load(look, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    const uint32_t flag = v >> 30;
-                    if (flag == 0) {
-                        if (++spins > SWEEP_SPIN_LIMIT) {
-                            fae_flag(a.status, FAE_STATUS_EINTERNAL);
+                bool done = false;
+                while (!done) {
+                    uint32_t v[8];
+#pragma unroll
+                    for (int q = 0; q < 8; ++q) {
+                        const int bq = back + q <= tl ? back + q : tl; // clamped into the table (tile tl back is its first)
+                        v[q] = __hip_atomic_load(st - (size_t)bq * RADIX, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    }
+#pragma unroll
+                    for (int q = 0; q < 8; ++q) {
+                        if (done || back > tl)
+                            break;
+                        const uint32_t flag = v[q] >> 30;
+                        if (flag == 0) { // not published yet: start the next round at this tile
+                            if (++spins > SWEEP_SPIN_LIMIT) {
+                                fae_flag(a.status, FAE_STATUS_EINTERNAL);
+                                done = true;
+                            } else {
+                                __builtin_amdgcn_s_sleep(1);
+                            }
                             break;
                         }
-                        __builtin_amdgcn_s_sleep(1);
-                        continue;
+                        before += v[q] & 0x3fffffffu;
+                        ++back;
+                        if (flag == SWEEP_PREFIX)
+                            done = true;
                     }
-                    before += v & 0x3fffffffu;
-                    if (flag == SWEEP_PREFIX)
-                        break;
-                    look -= RADIX; // the table's first tile publishes a running total, so this stops there
+                    if (back > tl)
+                        done = true; // cannot happen before a running total is met; keeps the walk inside the table
                 }
                 __hip_atomic_store(st, (SWEEP_PREFIX << 30) | (before + mine), __ATOMIC_RELAXED,
                                    __HIP_MEMORY_SCOPE_AGENT);
@@ -360,7 +383,7 @@ template <bool CHAINED> __global__ __launch_bounds__(SORT_THREADS) void sort_sca
     }
     __syncthreads();
 #pragma unroll
-    for (int i = 0; i < SORT_ITEMS; ++i) {
+    for (int i = 0; i < ITEMS; ++i) {
         if (base + i * FAE_WAVE + lane < seg1) {
             const int d = (key[i] >> a.shift) & a.mask;
             const int lp = wcnt[w][d] + off[i];
@@ -370,7 +393,7 @@ template <bool CHAINED> __global__ __launch_bounds__(SORT_THREADS) void sort_sca
     }
     __syncthreads();
 #pragma unroll
-    for (int i = 0; i < SORT_ITEMS; ++i) {
+    for (int i = 0; i < ITEMS; ++i) {
         const int lp = i * SORT_THREADS + threadIdx.x;
         if (lp < n_tile) {
             const int k = skey[lp];
@@ -939,6 +962,7 @@ namespace {
 struct BwdPlan {
     int64_t N;
     int64_t tiles;
+    int64_t small_tiles; // tiles of SORT_TILE_SMALL keys
     int64_t max_spans; // with the smallest span
     int64_t dbg_tiles;
 };
@@ -948,10 +972,12 @@ BwdPlan bwd_plan(int nt, const int64_t *h_n_lookups)
     BwdPlan p;
     p.N = 0;
     p.tiles = 0;
+    p.small_tiles = 0;
     p.max_spans = 0;
     for (int z = 0; z < nt; ++z) {
         p.N += h_n_lookups[z];
         p.tiles += (h_n_lookups[z] + SORT_TILE - 1) / SORT_TILE;
+        p.small_tiles += (h_n_lookups[z] + SORT_TILE_SMALL - 1) / SORT_TILE_SMALL;
         p.max_spans += (h_n_lookups[z] + BWD_SPAN_MIN - 1) / BWD_SPAN_MIN;
     }
     p.dbg_tiles = (p.N + DBG_TILE - 1) / DBG_TILE;
@@ -987,7 +1013,8 @@ BwdWs bwd_carve(void *ws, size_t bytes, const BwdPlan &p, int nt, int dim, int s
     }
     w.hist = cv.take<int32_t>((size_t)RADIX * p.tiles + 1);
     w.tot = cv.take<int32_t>((size_t)nt * RADIX);
-    w.sweep = cv.take<uint32_t>(64 + ((size_t)nt + (size_t)p.tiles) * SWEEP_MAX_PASSES * RADIX);
+    const size_t sweep_tiles = p.small_tiles <= SORT_SMALL_MAX_TILES ? (size_t)p.small_tiles : (size_t)p.tiles;
+    w.sweep = cv.take<uint32_t>(64 + ((size_t)nt + sweep_tiles) * SWEEP_MAX_PASSES * RADIX);
     w.partial = cv.take<float>((size_t)(p.max_spans * BWD_SPAN_MIN / span + nt + 1) * 2 * dim);
     w.dbg_tile_sums = cv.take<int32_t>((size_t)p.dbg_tiles + 2);
     w.dbg_rstart = cv.take<int32_t>((size_t)p.N + 2);
@@ -1160,6 +1187,18 @@ int32_t bwd_sort_stage(fae_ctx *ctx, hipStream_t st, const fae_tables *hot_table
     // The chained kernel's counters start at zero; the keys kernel fills the per-table digit
     // histograms of all passes.  sort_variant 1 forces the three-kernel passes, 3 the chained ones.
     const bool chained = passes > 0 && ctx->opt_sort != 1 && (ctx->opt_sort == 3 || tiles <= 4LL * ctx->n_cu);
+    // A chained pass over a short list takes small tiles: more workgroups, a shorter chain per tile
+    // (the same rule sizes the workspace, so it goes by the lookups of all tables).
+    const bool small_tiles = chained && su.plan.small_tiles <= SORT_SMALL_MAX_TILES;
+    if (small_tiles) {
+        tiles = 0;
+        for (int z = 0; z < nt; ++z) {
+            a.tile_start[z] = (int32_t)tiles;
+            if (!in_lds[z])
+                tiles += (hot_batch->h_n_lookups[z] + SORT_TILE_SMALL - 1) / SORT_TILE_SMALL;
+        }
+        a.tile_start[nt] = (int32_t)tiles;
+    }
     if (chained) {
         a.n_passes = passes;
         a.digit_bits = digit_bits;
@@ -1201,7 +1240,10 @@ int32_t bwd_sort_stage(fae_ctx *ctx, hipStream_t st, const fae_tables *hot_table
         a.vals_out = w.vals[cur ^ 1];
         if (chained) {
             fae_ktimer kt(ctx, FAE_K_SORT_SCATTER, st);
-            hipLaunchKernelGGL(sort_scatter_kernel<true>, dim3((unsigned)tiles), dim3(SORT_THREADS), 0, st, a);
+            if (small_tiles)
+                hipLaunchKernelGGL((sort_scatter_kernel<true, SORT_ITEMS_SMALL>), dim3((unsigned)tiles), dim3(SORT_THREADS), 0, st, a);
+            else
+                hipLaunchKernelGGL((sort_scatter_kernel<true, SORT_ITEMS>), dim3((unsigned)tiles), dim3(SORT_THREADS), 0, st, a);
             FAE_LAUNCH_CHECK(ctx);
             cur ^= 1;
             continue;
@@ -1218,7 +1260,7 @@ int32_t bwd_sort_stage(fae_ctx *ctx, hipStream_t st, const fae_tables *hot_table
         }
         {
             fae_ktimer kt(ctx, FAE_K_SORT_SCATTER, st);
-            hipLaunchKernelGGL(sort_scatter_kernel<false>, dim3((unsigned)tiles), dim3(SORT_THREADS), 0, st, a);
+            hipLaunchKernelGGL((sort_scatter_kernel<false, SORT_ITEMS>), dim3((unsigned)tiles), dim3(SORT_THREADS), 0, st, a);
             FAE_LAUNCH_CHECK(ctx);
         }
         cur ^= 1;
