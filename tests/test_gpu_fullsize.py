@@ -65,6 +65,20 @@ def test_full_size_workload(cfg_id):
     assert sum(n_hot) * D * 4 <= w.budget_bytes
     _log(f"cutoff ok: c={c}, hot rows={sum(n_hot)} ({sum(n_hot) * D * 4 / 2**30:.2f} GiB)")
 
+    # ---- sampled estimate of the hot size (Sec. 4.1.2, Eq. 2-4) at the chosen cutoffs ----------
+    chunks = [S.sample_chunks(w, z, 1024, 35) for z in range(nt)]
+    est, Cs = hp.estimate_hot(H, chunks, 1024, 0.999)
+    for z in range(nt):
+        assert Cs[z] == O.chunk_counts(cnts[z], 1024, chunks[z], H[z]).tolist(), f"chunk counts of table {z} differ"
+        if len(chunks[z]) >= 2:
+            rows, half, _, _ = O.estimate_hot_rows(cnts[z], 1024, chunks[z], H[z], 0.999)
+            assert abs(est[z]["rows"] - rows) <= 1e-12 * max(rows, 1.0)
+            assert abs(est[z]["half_rows"] - half) <= 1e-8 * max(half, 1.0)
+    cs_ref, Hs_ref = O.sampled_budget_cutoff(D, cnts, T_z, max(T_z), w.budget_bytes, w.small_table_bytes, 1024, chunks)
+    c_s, H_s, _ = hp.choose_cutoff_sampled(w.budget_bytes, chunks, 1024, 0.999, w.small_table_bytes)
+    assert (c_s, H_s) == (cs_ref, Hs_ref)
+    _log(f"sampled estimate ok: {sum(e['rows'] for e in est):.0f} rows estimated, {sum(n_hot)} exact; sampled search c={c_s}")
+
     # ---- a3 + a4: remap / hot ids in full, hot weights on sampled slots ----------------------
     assert hp.build(H, n_hot, seed=w.seed) == n_hot
     remap, hot_ids = [], []
@@ -160,3 +174,27 @@ def test_full_size_workload(cfg_id):
             got = hp.hotW[z][torch.from_numpy(cand).to(dev)].cpu().numpy()
             assert got.tobytes() == O.w0_rows(w.seed, z, hot_ids[z][cand].astype(np.int64), D).tobytes()
     _log("backward + SGD ok")
+
+    # ---- embedding synchronisation with full tables that fit the device (Sec. 3 (4), Sec. 6.2) ---
+    if sum(w.rows) * D * 4 <= (40 << 30):
+        full = [torch.zeros((r, D), dtype=torch.float32, device=dev) for r in w.rows]
+        hp.sync_to_full(full)
+        hp.sync()
+        for z in range(nt):
+            if n_hot[z] == 0:
+                continue
+            pick = np.unique(np.concatenate([rng.integers(0, n_hot[z], 2048), [0, n_hot[z] - 1]]))
+            rows_of = torch.from_numpy(hot_ids[z][pick].astype(np.int64)).to(dev)      # the ORACLE's slot -> row map
+            assert torch.equal(full[z][rows_of], hp.hotW[z][torch.from_numpy(pick).to(dev)]), f"hot -> full, table {z}"
+            cand = rng.integers(0, w.rows[z], 4096)
+            cand = np.unique(cand[remap[z][cand] < 0])
+            if cand.size:
+                assert not bool(full[z][torch.from_numpy(cand).to(dev)].any()), f"cold rows of table {z} were written"
+        kept = hp.hotW
+        hp.hotW = [torch.zeros_like(x) for x in kept]
+        hp.sync_from_full(full)
+        hp.sync()
+        for z in range(nt):
+            assert torch.equal(hp.hotW[z][:n_hot[z]], kept[z][:n_hot[z]]), f"full -> hot, table {z}"
+        del full, kept
+        _log("embedding synchronisation ok")
