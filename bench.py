@@ -41,6 +41,8 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--cpu-seconds", type=float, default=10.0)
     ap.add_argument("--set", action="append", default=[], help="library option name=value (ablation)")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture each step into a HIP graph and time the replays (same kernels, fewer launches)")
     ap.add_argument("--presort", choices=["fused", "side", "none"], default="fused",
                     help="where the backward's sort runs: in the forward's launch (default, where the shape "
                          "allows), on the side stream, or inside fae_embbag_bwd_sgd")
@@ -69,6 +71,8 @@ def run_workload(args, cfg_id, n_steps, n_warmup, with_cpu):
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = torch.device("cuda", 0)
+    if args.graph and torch.cuda.current_stream() == torch.cuda.default_stream():
+        torch.cuda.set_stream(torch.cuda.Stream())     # capture needs a stream of its own
     w = S.workload(cfg_id, "full")
     nt, D = w.n_tables, w.dim
     n_batches = args.batches or {1: 32, 2: 32, 3: 32, 4: 16, 5: 4}[cfg_id]
@@ -187,6 +191,21 @@ def run_workload(args, cfg_id, n_steps, n_warmup, with_cpu):
 
     # ---- timed region ----------------------------------------------------------------
     nb = len(steps_fn)
+    eager_fn = steps_fn
+    if args.graph:
+        for fn in steps_fn:
+            fn()
+        torch.cuda.synchronize()
+        # one graph holds the whole cycle of hot batches; step i of the timed loop replays it when
+        # i is the first batch of a cycle, so K steps need K rounded up to whole cycles of launches
+        cycle = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(cycle, stream=torch.cuda.current_stream()):
+            for fn in steps_fn:
+                fn()
+        if n_steps % nb or n_warmup % nb:
+            n_steps, n_warmup = max(nb, n_steps // nb * nb), n_warmup // nb * nb
+            log(f"graph mode: whole cycles of {nb} batches only -> {n_steps} steps, {n_warmup} warm-up")
+        steps_fn = [cycle.replay] + [lambda: None] * (nb - 1)
     for i in range(n_warmup):
         steps_fn[i % nb]()
     torch.cuda.synchronize()
@@ -207,7 +226,7 @@ def run_workload(args, cfg_id, n_steps, n_warmup, with_cpu):
     B.fae_timing_reset(hp.ctx)
     k_steps = min(n_steps, 200)
     for i in range(k_steps):
-        steps_fn[i % nb]()
+        eager_fn[i % nb]()
     torch.cuda.synchronize()
     kern = {}
     for k in range(B.FAE_K_COUNT):
@@ -300,7 +319,7 @@ def run_workload(args, cfg_id, n_steps, n_warmup, with_cpu):
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": w.name, "config_index": cfg_id, "tables": nt, "dim": D, "batch": w.batch,
                    "zipf_s": w.zipf_s, "hot_rows": int(sum(hp.n_hot)), "hot_bytes": int(sum(hp.n_hot)) * D * 4,
-                   "cutoff_c": c, "lookups_per_step": NL, "distinct_rows_per_step": U, "hot_batches": nb,
+                   "cutoff_c": c, "lookups_per_step": NL, "distinct_rows_per_step": U, "hot_batches": nb, "launch": "hip graph replay" if args.graph else "eager",
                    "profile_samples": w.profile_samples},
         "roofline": roofline, "cpu_baseline": cpu, "stages": {k: float(f"{v:.4g}") for k, v in stages.items()},
     }

@@ -44,9 +44,11 @@ class HotBatch:
 
 
 class HotPath:
-    def __init__(self, rows: Sequence[int], dim: int, device: int = 0):
+    def __init__(self, rows: Sequence[int], dim: int, device: int = 0, stream: Optional[int] = None):
+        """stream: a hipStream_t handle (e.g. ``torch.cuda.Stream().cuda_stream``); default is
+        torch's current stream at construction.  Every library call is queued there."""
         self.dev = torch.device("cuda", device)
-        self.ctx = B.Context(device)
+        self.ctx = B.Context(device, stream)
         self.tables = B.Tables(list(rows), dim)
         self.dim = dim
         self.nt = len(rows)
