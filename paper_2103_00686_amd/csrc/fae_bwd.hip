@@ -64,6 +64,9 @@ struct BwdArgs {
     int64_t gout_stride;
     float lr;
     float *partial;    // [total spans][2][dim]: sums of a span's first / last run when they cross its border
+    int32_t *flags;    // [n_flags] one word per span: its border sums are published (zeroed by the sort stage)
+    int32_t n_flags;
+    int32_t fused_fixup; // border-crossing runs are finished inside the reduce kernel
     int32_t span;      // lookups per wave in the reduce kernel
     int32_t n_spans;   // total spans (blk_start then holds the span prefix per table)
     uint32_t *status;
@@ -149,6 +152,23 @@ __device__ __forceinline__ void bwd_keys_thread(const BwdArgs &a, int z, int j0,
                 vo[q] = v[q];
             }
     }
+}
+
+// Every workgroup of a sort-stage kernel clears its slice of the span flags.  The slice length
+// comes from the host (whole 256-byte pieces, so that two workgroups never share a cache line):
+// reading the grid size on the device would put one more dependent scalar load in front of
+// workgroups that live for a few microseconds.
+__device__ __forceinline__ void bwd_clear_flags(int32_t *flags, int n_flags, int slice, int block_threads)
+{
+    const int beg = blockIdx.x * slice;
+    const int end = beg + slice < n_flags ? beg + slice : n_flags;
+    for (int i = beg + (int)threadIdx.x; i < end; i += block_threads)
+        flags[i] = 0;
+}
+static inline int bwd_flag_slice(int64_t n_flags, int64_t blocks)
+{
+    const int64_t per = blocks > 0 ? (n_flags + blocks - 1) / blocks : n_flags;
+    return (int)((per + 63) & ~(int64_t)63);
 }
 
 // Each thread handles four consecutive lookups (16-byte loads and stores when aligned).
@@ -427,10 +447,13 @@ struct LsortArgs {
     int32_t n_samples;
     int32_t *keys_out, *vals_out;
     uint32_t *status;
+    int32_t *flags; // span flags of the reduce kernel, zeroed here
+    int32_t n_flags, flag_slice;
 };
 
 __global__ __launch_bounds__(LSORT_THREADS) void lds_sort_kernel(LsortArgs a)
 {
+    bwd_clear_flags(a.flags, a.n_flags, a.flag_slice, LSORT_THREADS);
     const int z = fae_find_table(a.blk_start, a.n_tables, blockIdx.x);
     lds_sort_block(a.slots[z], a.offsets[z], a.seg_start[z + 1] - a.seg_start[z], a.n_hot[z],
                    blockIdx.x - a.blk_start[z], a.part_shift[z], a.n_samples, a.keys_out + a.seg_start[z],
@@ -485,6 +508,34 @@ template <> __device__ __forceinline__ float4 bwd_shfl<float4>(const float4 &v, 
                        __shfl(v.w, src, FAE_WAVE));
 }
 template <> __device__ __forceinline__ float bwd_shfl<float>(const float &v, int src) { return __shfl(v, src, FAE_WAVE); }
+
+// A slice of a border sum that another workgroup of the same launch reads: stored and loaded
+// word by word with device-scope atomics, which go past the caches that are private to a part
+// of the chip.  (Between two launches plain accesses are enough.)
+__device__ __forceinline__ void bwd_store_shared(float4 *p, const float4 &v)
+{
+    float *f = (float *)p;
+    __hip_atomic_store(f + 0, v.x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(f + 1, v.y, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(f + 2, v.z, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(f + 3, v.w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void bwd_store_shared(float *p, const float &v)
+{
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float4 bwd_load_shared(const float4 *p)
+{
+    const float *f = (const float *)p;
+    return make_float4(__hip_atomic_load(f + 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT),
+                       __hip_atomic_load(f + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT),
+                       __hip_atomic_load(f + 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT),
+                       __hip_atomic_load(f + 3, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+}
+__device__ __forceinline__ float bwd_load_shared(const float *p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
 
 // What a span knows about its borders (same predicate in the reduce and the fix-up kernel).
 struct SpanInfo {
@@ -621,16 +672,117 @@ template <typename V, int LPR> __global__ __launch_bounds__(256) void bwd_reduce
                     if (active) {
                         if (dest == 1)
                             W[(int64_t)kg * ncols + c] = bwd_vec<V>::sgd(ww[u], vg, step);
-                        else if (dest == 2)
-                            part[c] = vg;
-                        else if (dest == 3)
-                            part[ncols + c] = vg;
+                        else if (dest == 2) {
+                            if (a.fused_fixup)
+                                bwd_store_shared(&part[c], vg);
+                            else
+                                part[c] = vg;
+                        } else if (dest == 3) {
+                            if (a.fused_fixup)
+                                bwd_store_shared(&part[ncols + c], vg);
+                            else
+                                part[ncols + c] = vg;
+                        }
                     }
                     cv = vg; // used from the last group only
                 }
             }
         }
     }
+    if (!a.fused_fixup)
+        return;
+    // Runs that cross span borders are finished here, by the span in which they end: it adds the
+    // pieces the earlier spans have published (their tail sum where the run began, their whole-span
+    // sums in between) to its own head sum and applies the update.  It only ever waits for spans
+    // with smaller numbers, which were started before it; the wait is bounded all the same.
+    const int c = l; // one column slice per lane: the host takes this path only when the row fits LPR lanes
+    const bool active = c < ncols;
+    if (sp.head_open || sp.tail_open) {
+        __builtin_amdgcn_s_waitcnt(0x0F70); // vmcnt(0): this wave's border sums have been written
+        if (lane == 0)
+            __hip_atomic_store(&a.flags[sid], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    const bool closes_head = sp.head_open && !(sp.first_key == sp.last_key && sp.tail_open);
+    if (!closes_head || sp.first_key >= n_hot)
+        return;
+    const int k = sp.first_key;
+    V *wp = W + (int64_t)k * ncols + c;
+    V wv = bwd_vec<V>::zero();
+    float sw = 0.f;
+    if (g == 0 && active) {
+        wv = *wp;
+        if (a.adagrad)
+            sw = a.opt_state[sp.z][k];
+    }
+    // earlier spans that lie wholly inside the run: the lookup before their first one has the key too
+    int n_back = 0;
+    for (int base = 0;; base += FAE_WAVE) {
+        const int lm = sp.local - 1 - (base + lane);
+        const bool inside = lm > 0 && a.keys_in[sp.seg0 + lm * a.span - 1] == k;
+        const uint64_t m = __ballot(inside);
+        const int cnt = m == ~0ull ? FAE_WAVE : __builtin_ctzll(~m);
+        n_back += cnt;
+        if (cnt < FAE_WAVE)
+            break;
+    }
+    // pieces 0 .. n_back-1: whole-span sums of spans sid-1-t; piece n_back: tail sum of the span the run began in
+    V acc = bwd_vec<V>::zero();
+    constexpr int PB = 4; // pieces whose flags, then whose rows, are fetched together
+    for (int t0 = g; t0 <= n_back; t0 += PB * G) {
+        int spins = 0;
+        for (;;) { // until the pieces of this round are all published
+            int f[PB];
+#pragma unroll
+            for (int q = 0; q < PB; ++q) {
+                const int t = t0 + q * G;
+                f[q] = t <= n_back ? __hip_atomic_load(&a.flags[sid - 1 - t], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 1;
+            }
+            bool all = true;
+#pragma unroll
+            for (int q = 0; q < PB; ++q)
+                all = all && f[q] != 0;
+            if (all)
+                break;
+            if (++spins > SWEEP_SPIN_LIMIT) {
+                fae_flag(a.status, FAE_STATUS_EINTERNAL);
+                break;
+            }
+            __builtin_amdgcn_s_sleep(1);
+        }
+        V v[PB];
+#pragma unroll
+        for (int q = 0; q < PB; ++q) {
+            const int t = t0 + q * G;
+            v[q] = bwd_vec<V>::zero();
+            if (active && t <= n_back) {
+                const V *row = (const V *)(a.partial + ((int64_t)(sid - 1 - t) * 2 + (t == n_back ? 1 : 0)) * a.dim);
+                v[q] = bwd_load_shared(row + c);
+            }
+        }
+#pragma unroll
+        for (int q = 0; q < PB; ++q)
+            bwd_vec<V>::add(acc, v[q]);
+    }
+#pragma unroll
+    for (int mm = LPR; mm < FAE_WAVE; mm <<= 1) {
+        const V o = bwd_shfl<V>(acc, lane ^ mm);
+        bwd_vec<V>::add(acc, o);
+    }
+    if (g == 0 && active)
+        bwd_vec<V>::add(acc, bwd_load_shared(part + c)); // this span's own piece of the run
+    float step = a.lr;
+    if (a.adagrad) {
+        float q = active ? bwd_vec<V>::sumsq(acc) : 0.f;
+#pragma unroll
+        for (int mm = 1; mm < LPR; mm <<= 1)
+            q += __shfl_xor(q, mm, FAE_WAVE);
+        const float nacc = sw + q / (float)a.dim;
+        step = a.lr / (sqrtf(nacc) + a.eps);
+        if (g == 0 && l == 0)
+            a.opt_state[sp.z][k] = nacc;
+    }
+    if (g == 0 && active)
+        *wp = bwd_vec<V>::sgd(wv, acc, step);
 }
 
 // Segment reduce + SGD, second form: no traffic between lanes while the gradient rows are
@@ -998,6 +1150,8 @@ struct BwdWs {
     int32_t *hist, *tot;
     uint32_t *sweep; // ticket[64] | ghist[nt][SWEEP_MAX_PASSES][RADIX] | state[SWEEP_MAX_PASSES][tiles][RADIX]
     float *partial;
+    int32_t *flags;
+    int64_t n_flags;
     int32_t *dbg_tile_sums, *dbg_rstart;
     bool ok;
     size_t used;
@@ -1014,6 +1168,8 @@ BwdWs bwd_carve(void *ws, size_t bytes, const BwdPlan &p, int nt, int dim, int s
     w.hist = cv.take<int32_t>((size_t)RADIX * p.tiles + 1);
     w.tot = cv.take<int32_t>((size_t)nt * RADIX);
     const size_t sweep_tiles = p.small_tiles <= SORT_SMALL_MAX_TILES ? (size_t)p.small_tiles : (size_t)p.tiles;
+    w.n_flags = p.max_spans + nt + 1;
+    w.flags = cv.take<int32_t>((size_t)w.n_flags); // directly in front of the sweep area: one fill clears both
     w.sweep = cv.take<uint32_t>(64 + ((size_t)nt + sweep_tiles) * SWEEP_MAX_PASSES * RADIX);
     w.partial = cv.take<float>((size_t)(p.max_spans * BWD_SPAN_MIN / span + nt + 1) * 2 * dim);
     w.dbg_tile_sums = cv.take<int32_t>((size_t)p.dbg_tiles + 2);
@@ -1035,6 +1191,8 @@ template <typename V, int LPR> void launch_reduce(fae_ctx *ctx, const BwdArgs &a
         else
             hipLaunchKernelGGL((bwd_reduce_walk_kernel<V, LPR, 4>), grid, dim3(256), 0, ctx->stream, a);
     }
+    if (a.fused_fixup)
+        return;
     fae_ktimer kt(ctx, FAE_K_BWD_FIXUP);
     hipLaunchKernelGGL((bwd_fixup_kernel<V, LPR>), dim3((a.n_spans + 3) / 4), dim3(256), 0, ctx->stream, a);
 }
@@ -1111,6 +1269,8 @@ int32_t bwd_setup(fae_ctx *ctx, const fae_tables *hot_tables, const fae_batch *h
     a.hist = out->w.hist;
     a.tot = out->w.tot;
     a.partial = out->w.partial;
+    a.flags = out->w.flags;
+    a.n_flags = (int32_t)out->w.n_flags;
     a.status = ctx->d_block;
     return FAE_OK;
 }
@@ -1206,8 +1366,17 @@ int32_t bwd_sort_stage(fae_ctx *ctx, hipStream_t st, const fae_tables *hot_table
         a.ticket = (int32_t *)w.sweep;
         a.ghist = (int32_t *)w.sweep + 64;
         a.state = w.sweep + 64 + (size_t)nt * SWEEP_MAX_PASSES * RADIX;
-        int32_t rc = fae_fill_u32_on(ctx, st, w.sweep,
-                                     64 + ((int64_t)nt * SWEEP_MAX_PASSES + (int64_t)passes * tiles) * RADIX, 0u);
+    }
+    if (tiles > 0) {
+        // The span flags of the reduce kernel start at zero too.  The LDS sort clears them itself;
+        // a batch with tables on the global passes gets them cleared here, together with the
+        // chained passes' counters that follow them in the workspace.  (Clearing them in the keys
+        // kernel instead cost that kernel a third of its time.)
+        int64_t words = a.n_flags;
+        if (chained)
+            words = ((int32_t *)w.sweep - w.flags) +
+                    (64 + ((int64_t)nt * SWEEP_MAX_PASSES + (int64_t)passes * tiles) * RADIX);
+        int32_t rc = fae_fill_u32_on(ctx, st, w.flags, words, 0u);
         if (rc != FAE_OK)
             return rc;
     }
@@ -1285,6 +1454,9 @@ int32_t bwd_sort_stage(fae_ctx *ctx, hipStream_t st, const fae_tables *hot_table
         la.keys_out = w.keys[cur];
         la.vals_out = w.vals[cur];
         la.status = ctx->d_block;
+        la.flags = a.flags;
+        la.n_flags = a.n_flags;
+        la.flag_slice = bwd_flag_slice(a.n_flags, nb);
         fae_ktimer kt(ctx, FAE_K_LDS_SORT, st);
         hipLaunchKernelGGL(lds_sort_kernel, dim3(nb), dim3(LSORT_THREADS), 0, st, la);
         FAE_LAUNCH_CHECK(ctx);
@@ -1344,10 +1516,13 @@ struct FusedArgs {
     int32_t *keys_out, *vals_out;
     uint32_t *status;
     int32_t stream_out;
+    int32_t *flags; // span flags of the reduce kernel, zeroed here
+    int32_t n_flags, flag_slice;
 };
 
 template <typename V, int LPR> __global__ __launch_bounds__(LSORT_THREADS) void fwd_sort_kernel(FusedArgs a)
 {
+    bwd_clear_flags(a.flags, a.n_flags, a.flag_slice, LSORT_THREADS);
     if ((int)blockIdx.x < a.n_sort_blocks) {
         const int z = fae_find_table(a.sort_blk_start, a.n_tables, blockIdx.x);
         lds_sort_block(a.slots[z], nullptr, a.seg_start[z + 1] - a.seg_start[z], a.n_hot[z],
@@ -1409,7 +1584,10 @@ extern "C" int32_t fae_embbag_fwd_presort(fae_ctx *ctx, const fae_tables *hot_ta
     f.vals_out = su.w.vals[0];
     f.status = ctx->d_block;
     f.stream_out = ctx->opt_fwd_stream != 0;
+    f.flags = su.a.flags;
+    f.n_flags = su.a.n_flags;
     const int blocks = f.n_sort_blocks + f.fwd_blocks_per_table * nt;
+    f.flag_slice = bwd_flag_slice(f.n_flags, blocks);
     int lpr = 1;
     while (lpr < dim / 4 && lpr < 64)
         lpr <<= 1;
@@ -1558,6 +1736,10 @@ static int32_t bwd_impl(fae_ctx *ctx, const fae_tables *hot_tables, float *const
         }
         a.blk_start[nt] = (int32_t)spans;
         a.n_spans = (int32_t)spans;
+        // runs that cross span borders: finished inside the reduce kernel (scan form, rows that fit
+        // one pass over the lanes), else by the fix-up kernel
+        const bool scan_form = ctx->opt_reduce != 2 || a.mean || a.adagrad;
+        a.fused_fixup = ctx->opt_fixup != 1 && scan_form && ncols <= lpr && spans <= a.n_flags;
 #define CALL_REDUCE(V, L) launch_reduce<V, L>(ctx, a)
         if (vec) {
             BWD_LPR_SWITCH(float4, lpr, CALL_REDUCE)

@@ -217,6 +217,8 @@ extern "C" int32_t fae_set_option(fae_ctx *ctx, const char *name, int64_t value)
         ctx->opt_fwd_stream = value;
     else if (!strcmp(name, "reduce_span") && (value == 0 || value == 64 || value == 128 || value == 256))
         ctx->opt_span = value;
+    else if (!strcmp(name, "fixup_variant") && value >= 0 && value <= 1)
+        ctx->opt_fixup = value;
     else if (!strcmp(name, "reduce_variant") && value >= 0 && value <= 2)
         ctx->opt_reduce = value;
     else if (!strcmp(name, "reduce_unroll") && (value == 0 || value == 4 || value == 8))
