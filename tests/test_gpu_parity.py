@@ -46,13 +46,16 @@ def test_workload_end_to_end(dev, cfg_id, materialise):
 
 
 @pytest.mark.parametrize("cfg_id", [2, 3, 5])
-@pytest.mark.parametrize("reduce_variant,unroll,span", [(1, 0, 0), (2, 0, 0), (2, 4, 64), (2, 8, 256), (2, 8, 128)])
-def test_reduce_variants(dev, cfg_id, reduce_variant, unroll, span):
-    """Both forms of the segment reduce, every load depth and span length, on one-hot and
-    multi-hot workloads; two steps, so the second sees rows the first has changed."""
+@pytest.mark.parametrize("reduce_variant,unroll,span,fixup", [(1, 0, 0, 0), (1, 0, 64, 0), (1, 0, 256, 0), (1, 0, 0, 1), (2, 0, 0, 0),
+                                                              (2, 4, 64, 0), (2, 8, 256, 0), (2, 8, 128, 1)])
+def test_reduce_variants(dev, cfg_id, reduce_variant, unroll, span, fixup):
+    """Both forms of the segment reduce, every load depth and span length, border-crossing runs
+    finished inside the kernel or by the fix-up kernel, on one-hot and multi-hot workloads; two
+    steps, so the second sees rows the first has changed."""
     w = S.workload(cfg_id, "test")
     p = T.Pipeline(w, dev, profile_chunks=1)
-    for k, v in (("reduce_variant", reduce_variant), ("reduce_unroll", unroll), ("reduce_span", span)):
+    for k, v in (("reduce_variant", reduce_variant), ("reduce_unroll", unroll), ("reduce_span", span),
+                 ("fixup_variant", fixup)):
         B.fae_set_option(p.hp.ctx, k, v)
     p.check_profile()
     p.check_cutoff()
@@ -116,9 +119,11 @@ def test_forward_backward_shapes(dev, variant, dim):
         assert got[mask].tobytes() == before[z][mask].tobytes()
 
 
-@pytest.mark.parametrize("S_,sort_variant,reduce_variant", [(50_000, 0, 1), (50_000, 1, 2), (50_000, 3, 2), (300_000, 0, 2),
-                                                            (300_000, 1, 1), (50_000, 0, 2)])
-def test_backward_long_runs_and_many_tiles(dev, S_, sort_variant, reduce_variant):
+@pytest.mark.parametrize("S_,sort_variant,reduce_variant,span,fixup",
+                         [(50_000, 0, 1, 0, 0), (50_000, 0, 1, 64, 0), (50_000, 0, 1, 256, 1), (50_000, 1, 2, 0, 0),
+                          (50_000, 3, 2, 0, 0), (300_000, 0, 2, 0, 0), (300_000, 1, 1, 64, 0), (300_000, 3, 1, 0, 1),
+                          (50_000, 0, 2, 0, 0)])
+def test_backward_long_runs_and_many_tiles(dev, S_, sort_variant, reduce_variant, span, fixup):
     """One slot repeated tens of thousands of times (a run that crosses hundreds of spans and, in
     the key-range sort, a single value larger than the LDS buffers), runs of about two spans,
     several sort tiles, three radix passes.  50 000 lookups take the key-range sort (or the
@@ -137,6 +142,8 @@ def test_backward_long_runs_and_many_tiles(dev, S_, sort_variant, reduce_variant
     hp = HotPath([n_hot], dim, 0)
     B.fae_set_option(hp.ctx, "sort_variant", sort_variant)
     B.fae_set_option(hp.ctx, "reduce_variant", reduce_variant)
+    B.fae_set_option(hp.ctx, "reduce_span", span)
+    B.fae_set_option(hp.ctx, "fixup_variant", fixup)
     hp.n_hot = [n_hot]
     hp.hotW = [torch.zeros((n_hot, dim), dtype=torch.float32, device=dev)]
     w_rows = (rng.random((rows.size, dim), dtype=np.float32) - 0.5)

@@ -78,13 +78,15 @@ def _adagrad_bound(G, Ga, w_old, st_old, lr, eps, dim):
     return 2 * bw, 2 * da
 
 
+@pytest.mark.parametrize("fixup", [0, 1])
 @pytest.mark.parametrize("dim", [64, 20, 128, 4])
 @pytest.mark.parametrize("pooling,optimizer", [(B.FAE_POOL_MEAN, B.FAE_OPT_SGD), (B.FAE_POOL_SUM, B.FAE_OPT_ROWWISE_ADAGRAD),
                                                (B.FAE_POOL_MEAN, B.FAE_OPT_ROWWISE_ADAGRAD)])
-def test_backward_variants(dev, dim, pooling, optimizer):
+def test_backward_variants(dev, dim, pooling, optimizer, fixup):
     rng = np.random.default_rng(300 + dim + 7 * pooling + 13 * optimizer)
     n_hot, S_, lr, eps = [900, 50, 3000], 700, 0.05, 1e-3
     hp = HotPath(n_hot, dim, 0)
+    B.fae_set_option(hp.ctx, "fixup_variant", fixup)       # border-crossing runs: inside the reduce kernel / fix-up kernel
     hp.n_hot = n_hot
     Wref = [(rng.random((n, dim), dtype=np.float32) - 0.5) for n in n_hot]
     Sref = [np.zeros(n, np.float32) for n in n_hot]
