@@ -325,6 +325,15 @@ def run_workload(args, cfg_id, n_steps, n_warmup, with_cpu):
     }
     # measured HBM traffic of the dominant kernel, if a counter summary for it is committed
     roofline["traffic"] = committed_traffic(cfg_id, dom)
+    # measured HBM traffic of the whole step: committed per-launch figures of every kernel the step
+    # launches, times launches per step, over the step time measured here (null if a kernel has none)
+    per = {k: committed_traffic(cfg_id, k) for k in kern if k not in ("fill",)}
+    if per and all(v is not None for v in per.values()):
+        tb = sum(per[k] * kern[k]["launches_per_step"] for k in per)
+        roofline["step_traffic_bytes"] = int(tb)
+        roofline["step_traffic_frac"] = round(tb / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)
+    else:
+        roofline["step_traffic_bytes"] = roofline["step_traffic_frac"] = None
     del steps_fn, batches, gouts, outs, hp
     torch.cuda.empty_cache()
     return line
