@@ -2,17 +2,20 @@
 // embedding update on the GPU for hot mini-batches).
 //
 //   1. keys    key = hot slot, value = sample id, per table segment
-//   2. sort    stable LSD radix sort of (key, value), segmented by table; only the
-//              bits a hot slot can occupy are sorted
+//   2. sort    stable sort of (key, value), segmented by table: inside LDS for tables of up
+//              to 16 K lookups, else LSD radix passes over only the bits a hot slot can
+//              occupy (one chained kernel per pass for short lists, three kernels per pass
+//              for long ones)
 //   3. reduce  one wave owns a span of the sorted lookups.  Its 64/LPR lane groups
-//              take consecutive lookups (LPR lanes x 16 B cover one gradient row), a
-//              segmented scan over the groups plus a carried (key, sum) pair sums
-//              each run of equal keys; a run that lies inside the span gets its SGD
-//              update w -= lr * G at once.  All gradient loads of a span are
-//              independent of the run structure, so they pipeline freely.
-//   4. fix-up  the first / last run of a span may continue in the neighbours: those
-//              sums go to a small scratch array and one lane group per crossing run
-//              adds them in span order and applies the update.
+//              take consecutive lookups (LPR lanes x 16 B cover one gradient row); a
+//              segmented scan over the groups, which also hands on the sum carried
+//              from the previous step, sums each run of equal keys; a run that lies
+//              inside the span gets its update w -= lr * G at once.  All gradient loads
+//              of a span are independent of the run structure, so they pipeline freely.
+//   4. borders the first / last run of a span may continue in the neighbours: those
+//              sums are published in a small scratch array and the span in which the
+//              run ends adds them in span order and applies the update (inside the
+//              reduce kernel; as a kernel of its own for very wide rows or on request).
 // No float atomics: every row has exactly one writer and a fixed summation order.
 // Bandwidth bound: per lookup one gradient row is read, per distinct row one weight
 // row is read and written; the sort moves 16 B per lookup and pass.
@@ -461,7 +464,7 @@ __global__ __launch_bounds__(LSORT_THREADS) void lds_sort_kernel(LsortArgs a)
 }
 
 // ---------------------------------------------------------------------------------
-// 3. segment reduce + SGD for runs that start inside a chunk
+// 3 + 4. segment reduce + optimizer step
 // ---------------------------------------------------------------------------------
 template <typename V> struct bwd_vec;
 template <> struct bwd_vec<float4> {
