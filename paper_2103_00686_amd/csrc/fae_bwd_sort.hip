@@ -409,6 +409,23 @@ int32_t bwd_sort_stage(fae_ctx *ctx, hipStream_t st, const fae_tables *hot_table
     for (int z = 0; z < nt; ++z) {
         const int64_t nl = hot_batch->h_n_lookups[z];
         in_lds[z] = ctx->opt_sort != 1 && nl > 0 && nl <= LSORT_MAX;
+        if (!in_lds[z] && nl > 0 && hot_tables->h_rows[z] > max_hot_global)
+            max_hot_global = hot_tables->h_rows[z];
+    }
+    // When some table needs the global passes anyway, a small table whose slots need no more
+    // passes than those rides along: its few tiles cost nothing there, and if no small table is
+    // left the LDS sort (a launch of its own, ~10 us however small the table) is not needed.
+    if (max_hot_global > 0 && ctx->opt_sort != 2) {
+        int gbits = 1;
+        while ((max_hot_global >> gbits) != 0)
+            ++gbits;
+        const int gpasses = (gbits + RADIX_BITS - 1) / RADIX_BITS;
+        for (int z = 0; z < nt; ++z)
+            if (in_lds[z] && hot_tables->h_rows[z] < (1LL << (gpasses * RADIX_BITS)))
+                in_lds[z] = false;
+    }
+    for (int z = 0; z < nt; ++z) {
+        const int64_t nl = hot_batch->h_n_lookups[z];
         if (in_lds[z])
             ++n_lds;
         else if (nl > 0 && hot_tables->h_rows[z] > max_hot_global)
