@@ -38,7 +38,8 @@ struct BwdArgs {
     int32_t *tot;  // [n_tables][RADIX]
     // single-kernel passes (chained tile prefixes)
     int32_t pass, n_passes, digit_bits, total_tiles;
-    int32_t *ticket;   // [SWEEP_MAX_PASSES] next tile to hand out, per pass
+    int32_t *ticket;   // [SWEEP_MAX_PASSES] next tile to hand out, per pass (use_ticket only)
+    int32_t use_ticket; // chained passes: tiles are handed out by a counter instead of by workgroup number
     int32_t *ghist;    // [n_tables][SWEEP_MAX_PASSES][RADIX] digit counts of a table, per pass
     uint32_t *state;   // [SWEEP_MAX_PASSES][total_tiles][RADIX] flag (2 bits) | count (30 bits)
     // pooling / optimizer variants

@@ -177,12 +177,14 @@ __global__ __launch_bounds__(256) void sort_colscan_kernel(BwdArgs a)
 //
 // ITEMS = keys per thread (a tile is 256 * ITEMS keys).
 // CHAINED = false: the tile's output offsets come from the histogram / column-scan kernels.
-// CHAINED = true : the whole pass is this one kernel.  Tiles are handed out in order by a
-// ticket counter; a tile publishes its digit counts, then adds up the published counts of
-// the tiles before it (walking back until it meets a tile that already published its
-// running total) and publishes its own running total.  A tile only ever waits for tiles
-// with smaller tickets, which are already running, so every wait ends; the wait is bounded
-// anyway and reports an internal error instead of spinning forever.
+// CHAINED = true : the whole pass is this one kernel.  A tile publishes its digit counts,
+// then adds up the published counts of the tiles before it (walking back until it meets a
+// tile that already published its running total) and publishes its own running total.  A
+// tile only ever waits for tiles with smaller workgroup numbers, which the hardware starts
+// first; the wait is bounded all the same and reports an internal error instead of spinning
+// forever.  (Handing tiles out through a counter instead makes the order certain but costs
+// ~35 ns per workgroup, one device-wide atomic after the other: half the time of a pass over
+// a short list.  sort_variant 4 does it that way.)
 template <bool CHAINED, int ITEMS> __global__ __launch_bounds__(SORT_THREADS) void sort_scatter_kernel(BwdArgs a)
 {
     constexpr int TILE = SORT_THREADS * ITEMS;
@@ -193,7 +195,7 @@ template <bool CHAINED, int ITEMS> __global__ __launch_bounds__(SORT_THREADS) vo
     __shared__ int scan_lds[SORT_THREADS / FAE_WAVE + 1];
     __shared__ int s_tile;
     int tile = blockIdx.x;
-    if (CHAINED) {
+    if (CHAINED && a.use_ticket) {
         if (threadIdx.x == 0)
             s_tile = atomicAdd(&a.ticket[a.pass], 1);
         __syncthreads();
@@ -447,7 +449,9 @@ int32_t bwd_sort_stage(fae_ctx *ctx, hipStream_t st, const fae_tables *hot_table
     // (measured: 59 us against 63 us per pass at 10.5 M lookups, 16 us against 30 us at 0.2 M).
     // The chained kernel's counters start at zero; the keys kernel fills the per-table digit
     // histograms of all passes.  sort_variant 1 forces the three-kernel passes, 3 the chained ones.
-    const bool chained = passes > 0 && ctx->opt_sort != 1 && (ctx->opt_sort == 3 || tiles <= 4LL * ctx->n_cu);
+    const bool chained =
+        passes > 0 && ctx->opt_sort != 1 && (ctx->opt_sort == 3 || ctx->opt_sort == 4 || tiles <= 4LL * ctx->n_cu);
+    a.use_ticket = ctx->opt_sort == 4;
     // A chained pass over a short list takes small tiles: more workgroups, a shorter chain per tile
     // (the same rule sizes the workspace, so it goes by the lookups of all tables).
     const bool small_tiles = chained && su.plan.small_tiles <= SORT_SMALL_MAX_TILES;

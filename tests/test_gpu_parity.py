@@ -121,7 +121,7 @@ def test_forward_backward_shapes(dev, variant, dim):
 
 @pytest.mark.parametrize("S_,sort_variant,reduce_variant,span,fixup",
                          [(50_000, 0, 1, 0, 0), (50_000, 0, 1, 64, 0), (50_000, 0, 1, 256, 1), (50_000, 1, 2, 0, 0),
-                          (50_000, 3, 2, 0, 0), (300_000, 0, 2, 0, 0), (300_000, 1, 1, 64, 0), (300_000, 3, 1, 0, 1),
+                          (50_000, 3, 2, 0, 0), (300_000, 0, 2, 0, 0), (300_000, 1, 1, 64, 0), (300_000, 3, 1, 0, 1), (300_000, 4, 1, 0, 0),
                           (50_000, 0, 2, 0, 0)])
 def test_backward_long_runs_and_many_tiles(dev, S_, sort_variant, reduce_variant, span, fixup):
     """One slot repeated tens of thousands of times (a run that crosses hundreds of spans and, in
