@@ -107,7 +107,8 @@ int32_t fae_sync(fae_ctx *ctx);
  * by a counter), ("reduce_variant", 0=auto
  * 1=segmented scan across lane groups 2=a share of the span per lane group),
  * ("reduce_span", 0/64/128/256 sorted lookups per wave), ("reduce_unroll", 0/4/8 gradient
- * rows in flight per lane group, second form only), ("fixup_variant", 0=auto: runs that
+ * rows in flight per lane group, second form only), ("reduce_wg_waves", 0=auto (1)/1/2/4
+ * waves per workgroup of the reduce kernel), ("fixup_variant", 0=auto: runs that
  * cross the reduce kernel's spans are finished inside it, 1=by a kernel of their own),
  * ("fwd_stream_out", 0/1). */
 int32_t fae_set_option(fae_ctx *ctx, const char *name, int64_t value);

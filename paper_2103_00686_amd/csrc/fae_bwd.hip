@@ -168,6 +168,23 @@ extern "C" int32_t fae_embbag_bwd_opts(fae_ctx *ctx, const fae_tables *hot_table
     return bwd_impl(ctx, hot_tables, h_hotW, hot_batch, gout, gout_row_stride, *opts, dbg, ws, ws_bytes);
 }
 
+// The second form of the reduce kernel addresses rows with 24-bit by 24-bit multiplies and 32-bit byte offsets
+// and handles float4 columns that fit one pass over a lane group of 4 to 64 lanes: true where all of
+// that holds.
+static bool bwd_walk_fits(const fae_tables *hot_tables, const fae_batch *hot_batch, int64_t gout_row_stride,
+                          bool vec, int ncols, int lpr)
+{
+    const int64_t lim24 = (int64_t)1 << 24, lim32 = (int64_t)1 << 32;
+    const int64_t rowb = (int64_t)hot_tables->dim * 4, gstrideb = gout_row_stride * 4;
+    if (!vec || ncols > lpr || lpr < 4 || rowb >= lim24 || gstrideb >= lim24 || hot_batch->n_samples > lim24 ||
+        hot_batch->n_samples * gstrideb >= lim32)
+        return false;
+    for (int z = 0; z < hot_tables->n_tables; ++z)
+        if (hot_tables->h_rows[z] > lim24 || hot_tables->h_rows[z] * rowb >= lim32)
+            return false;
+    return true;
+}
+
 static int32_t bwd_impl(fae_ctx *ctx, const fae_tables *hot_tables, float *const *h_hotW,
                         const fae_batch *hot_batch, const float *gout, int64_t gout_row_stride,
                         const fae_step_opts &opts, const fae_bwd_debug *dbg, void *ws, size_t ws_bytes)
@@ -257,8 +274,14 @@ static int32_t bwd_impl(fae_ctx *ctx, const fae_tables *hot_tables, float *const
         a.n_spans = (int32_t)spans;
         // runs that cross span borders: finished inside the reduce kernel (scan form, rows that fit
         // one pass over the lanes), else by the fix-up kernel
-        const bool scan_form = ctx->opt_reduce != 2 || a.mean || a.adagrad;
-        a.fused_fixup = ctx->opt_fixup != 1 && scan_form && ncols <= lpr && spans <= a.n_flags;
+        a.form = 0;
+        // one wave per workgroup unless asked otherwise: the waves of a launch then spread evenly
+        // over the compute units whatever the number of spans is
+        a.wg_waves = ctx->opt_wg_waves ? (int32_t)ctx->opt_wg_waves : 1;
+        if (ctx->opt_reduce == 2 && !a.mean && !a.adagrad &&
+            bwd_walk_fits(hot_tables, hot_batch, gout_row_stride, vec, ncols, lpr))
+            a.form = 1;
+        a.fused_fixup = ctx->opt_fixup != 1 && ncols <= lpr && spans <= a.n_flags;
         bwd_launch_reduce(ctx, a, vec, lpr);
         FAE_LAUNCH_CHECK(ctx);
     }

@@ -107,13 +107,114 @@ __device__ __forceinline__ SpanInfo bwd_span_info(const BwdArgs &a, int sid)
     return s;
 }
 
+// Runs that cross span borders are finished by the span in which they end: it adds the pieces
+// the earlier spans have published (their tail sum where the run began, their whole-span sums in
+// between) to its own head sum and applies the update.  It only ever waits for spans with smaller
+// numbers, which were started before it; the wait is bounded all the same.  Called by every wave
+// once its own border sums have been stored with bwd_store_shared.
+template <typename V, int LPR>
+__device__ __forceinline__ void bwd_finish_borders(const BwdArgs &a, const SpanInfo &sp, int sid, int n_hot, V *W,
+                                                   V *part, int ncols)
+{
+    constexpr int G = FAE_WAVE / LPR;
+    const int lane = fae_lane(), g = lane / LPR, l = lane % LPR;
+    const int c = l; // one column slice per lane: the host takes this path only when the row fits LPR lanes
+    const bool active = c < ncols;
+    if (sp.head_open || sp.tail_open) {
+        __builtin_amdgcn_s_waitcnt(0x0F70); // vmcnt(0): this wave's border sums have been written
+        if (lane == 0)
+            __hip_atomic_store(&a.flags[sid], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    const bool closes_head = sp.head_open && !(sp.first_key == sp.last_key && sp.tail_open);
+    if (!closes_head || sp.first_key >= n_hot)
+        return;
+    const int k = sp.first_key;
+    V *wp = W + (int64_t)k * ncols + c;
+    V wv = bwd_vec<V>::zero();
+    float sw = 0.f;
+    if (g == 0 && active) {
+        wv = *wp;
+        if (a.adagrad)
+            sw = a.opt_state[sp.z][k];
+    }
+    // earlier spans that lie wholly inside the run: the lookup before their first one has the key too
+    int n_back = 0;
+    for (int base = 0;; base += FAE_WAVE) {
+        const int lm = sp.local - 1 - (base + lane);
+        const bool inside = lm > 0 && a.keys_in[sp.seg0 + lm * a.span - 1] == k;
+        const uint64_t m = __ballot(inside);
+        const int cnt = m == ~0ull ? FAE_WAVE : __builtin_ctzll(~m);
+        n_back += cnt;
+        if (cnt < FAE_WAVE)
+            break;
+    }
+    // pieces 0 .. n_back-1: whole-span sums of spans sid-1-t; piece n_back: tail sum of the span the run began in
+    V acc = bwd_vec<V>::zero();
+    constexpr int PB = 4; // pieces whose flags, then whose rows, are fetched together
+    for (int t0 = g; t0 <= n_back; t0 += PB * G) {
+        int spins = 0;
+        for (;;) { // until the pieces of this round are all published
+            int f[PB];
+#pragma unroll
+            for (int q = 0; q < PB; ++q) {
+                const int t = t0 + q * G;
+                f[q] = t <= n_back ? __hip_atomic_load(&a.flags[sid - 1 - t], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 1;
+            }
+            bool all = true;
+#pragma unroll
+            for (int q = 0; q < PB; ++q)
+                all = all && f[q] != 0;
+            if (all)
+                break;
+            if (++spins > SWEEP_SPIN_LIMIT) {
+                fae_flag(a.status, FAE_STATUS_EINTERNAL);
+                break;
+            }
+            __builtin_amdgcn_s_sleep(1);
+        }
+        V v[PB];
+#pragma unroll
+        for (int q = 0; q < PB; ++q) {
+            const int t = t0 + q * G;
+            v[q] = bwd_vec<V>::zero();
+            if (active && t <= n_back) {
+                const V *row = (const V *)(a.partial + ((int64_t)(sid - 1 - t) * 2 + (t == n_back ? 1 : 0)) * a.dim);
+                v[q] = bwd_load_shared(row + c);
+            }
+        }
+#pragma unroll
+        for (int q = 0; q < PB; ++q)
+            bwd_vec<V>::add(acc, v[q]);
+    }
+#pragma unroll
+    for (int mm = LPR; mm < FAE_WAVE; mm <<= 1) {
+        const V o = bwd_shfl<V>(acc, lane ^ mm);
+        bwd_vec<V>::add(acc, o);
+    }
+    if (g == 0 && active)
+        bwd_vec<V>::add(acc, bwd_load_shared(part + c)); // this span's own piece of the run
+    float step = a.lr;
+    if (a.adagrad) {
+        float q = active ? bwd_vec<V>::sumsq(acc) : 0.f;
+#pragma unroll
+        for (int mm = 1; mm < LPR; mm <<= 1)
+            q += __shfl_xor(q, mm, FAE_WAVE);
+        const float nacc = sw + q / (float)a.dim;
+        step = a.lr / (sqrtf(nacc) + a.eps);
+        if (g == 0 && l == 0)
+            a.opt_state[sp.z][k] = nacc;
+    }
+    if (g == 0 && active)
+        *wp = bwd_vec<V>::sgd(wv, acc, step);
+}
+
 template <typename V, int LPR> __global__ __launch_bounds__(256) void bwd_reduce_kernel(BwdArgs a)
 {
     constexpr int G = FAE_WAVE / LPR;              // lane groups = gradient rows per step
     constexpr int VW = sizeof(V) / sizeof(float);
     constexpr int STEPS = FAE_WAVE / G;            // steps per tile of 64 lookups
     constexpr int UN = STEPS < 4 ? STEPS : 4;      // steps whose loads are issued together
-    const int sid = blockIdx.x * (256 / FAE_WAVE) + threadIdx.x / FAE_WAVE;
+    const int sid = blockIdx.x * a.wg_waves + threadIdx.x / FAE_WAVE;
     if (sid >= a.n_spans)
         return;
     const SpanInfo sp = bwd_span_info(a, sid);
@@ -234,280 +335,186 @@ template <typename V, int LPR> __global__ __launch_bounds__(256) void bwd_reduce
             }
         }
     }
-    if (!a.fused_fixup)
-        return;
-    // Runs that cross span borders are finished here, by the span in which they end: it adds the
-    // pieces the earlier spans have published (their tail sum where the run began, their whole-span
-    // sums in between) to its own head sum and applies the update.  It only ever waits for spans
-    // with smaller numbers, which were started before it; the wait is bounded all the same.
-    const int c = l; // one column slice per lane: the host takes this path only when the row fits LPR lanes
-    const bool active = c < ncols;
-    if (sp.head_open || sp.tail_open) {
-        __builtin_amdgcn_s_waitcnt(0x0F70); // vmcnt(0): this wave's border sums have been written
-        if (lane == 0)
-            __hip_atomic_store(&a.flags[sid], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    }
-    const bool closes_head = sp.head_open && !(sp.first_key == sp.last_key && sp.tail_open);
-    if (!closes_head || sp.first_key >= n_hot)
-        return;
-    const int k = sp.first_key;
-    V *wp = W + (int64_t)k * ncols + c;
-    V wv = bwd_vec<V>::zero();
-    float sw = 0.f;
-    if (g == 0 && active) {
-        wv = *wp;
-        if (a.adagrad)
-            sw = a.opt_state[sp.z][k];
-    }
-    // earlier spans that lie wholly inside the run: the lookup before their first one has the key too
-    int n_back = 0;
-    for (int base = 0;; base += FAE_WAVE) {
-        const int lm = sp.local - 1 - (base + lane);
-        const bool inside = lm > 0 && a.keys_in[sp.seg0 + lm * a.span - 1] == k;
-        const uint64_t m = __ballot(inside);
-        const int cnt = m == ~0ull ? FAE_WAVE : __builtin_ctzll(~m);
-        n_back += cnt;
-        if (cnt < FAE_WAVE)
-            break;
-    }
-    // pieces 0 .. n_back-1: whole-span sums of spans sid-1-t; piece n_back: tail sum of the span the run began in
-    V acc = bwd_vec<V>::zero();
-    constexpr int PB = 4; // pieces whose flags, then whose rows, are fetched together
-    for (int t0 = g; t0 <= n_back; t0 += PB * G) {
-        int spins = 0;
-        for (;;) { // until the pieces of this round are all published
-            int f[PB];
-#pragma unroll
-            for (int q = 0; q < PB; ++q) {
-                const int t = t0 + q * G;
-                f[q] = t <= n_back ? __hip_atomic_load(&a.flags[sid - 1 - t], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 1;
-            }
-            bool all = true;
-#pragma unroll
-            for (int q = 0; q < PB; ++q)
-                all = all && f[q] != 0;
-            if (all)
-                break;
-            if (++spins > SWEEP_SPIN_LIMIT) {
-                fae_flag(a.status, FAE_STATUS_EINTERNAL);
-                break;
-            }
-            __builtin_amdgcn_s_sleep(1);
-        }
-        V v[PB];
-#pragma unroll
-        for (int q = 0; q < PB; ++q) {
-            const int t = t0 + q * G;
-            v[q] = bwd_vec<V>::zero();
-            if (active && t <= n_back) {
-                const V *row = (const V *)(a.partial + ((int64_t)(sid - 1 - t) * 2 + (t == n_back ? 1 : 0)) * a.dim);
-                v[q] = bwd_load_shared(row + c);
-            }
-        }
-#pragma unroll
-        for (int q = 0; q < PB; ++q)
-            bwd_vec<V>::add(acc, v[q]);
-    }
-#pragma unroll
-    for (int mm = LPR; mm < FAE_WAVE; mm <<= 1) {
-        const V o = bwd_shfl<V>(acc, lane ^ mm);
-        bwd_vec<V>::add(acc, o);
-    }
-    if (g == 0 && active)
-        bwd_vec<V>::add(acc, bwd_load_shared(part + c)); // this span's own piece of the run
-    float step = a.lr;
-    if (a.adagrad) {
-        float q = active ? bwd_vec<V>::sumsq(acc) : 0.f;
-#pragma unroll
-        for (int mm = 1; mm < LPR; mm <<= 1)
-            q += __shfl_xor(q, mm, FAE_WAVE);
-        const float nacc = sw + q / (float)a.dim;
-        step = a.lr / (sqrtf(nacc) + a.eps);
-        if (g == 0 && l == 0)
-            a.opt_state[sp.z][k] = nacc;
-    }
-    if (g == 0 && active)
-        *wp = bwd_vec<V>::sgd(wv, acc, step);
+    if (a.fused_fixup)
+        bwd_finish_borders<V, LPR>(a, sp, sid, n_hot, W, part, ncols);
 }
 
 // Segment reduce + SGD, second form: no traffic between lanes while the gradient rows are
-// summed.  A wave still owns a span of sorted lookups, but each of its 64/LPR lane groups walks
-// its own contiguous share of the span: NB gradient rows in flight per group and a running sum
-// per run.  The (slot, sample) pairs are fetched one batch ahead (the same address in all lanes
-// of a group), so the shape of the runs is known when a batch's loads are issued: the weight
-// row of every run that closes strictly inside the share is loaded together with the gradient
-// rows and updated as soon as the run's sum is complete.  What is left per group is its first
-// and its last run; one pass over the groups, in order, joins those that continue each other
-// and sends every joined run to its place: the weight row (preloaded by the group in which the
-// run ends), or the span's head / tail scratch row when the run crosses the span's border (the
-// fix-up kernel adds those up in span order, so the result does not depend on timing).
-template <typename V, int LPR, int NB> __global__ __launch_bounds__(256) void bwd_reduce_walk_kernel(BwdArgs a)
+// summed, and as few instructions per gradient row as it takes.  A wave still owns a span of
+// sorted lookups, but each of its 64/LPR lane groups walks its own contiguous share of the span,
+// NB gradient rows in flight per group and a running sum per run (kept with selects).  The wave
+// copies the (slot, sample) pairs of its span into LDS once (coalesced) and each group reads the
+// pairs of its share from there four at a time (one address per group, a broadcast), so the shape
+// of the runs is known when a batch's loads are issued: the weight row of every run that closes
+// strictly inside the share is loaded together with the gradient rows and updated as soon as the
+// run's sum is complete.  Rows are addressed with a 32-bit byte offset from the table's or the
+// gradient's base (the host takes this form only where every offset fits: see bwd_walk_fits).
+// What is left per group is its first and its last run; one pass over the groups, in order,
+// joins those that continue each other and sends every joined run to its place: the weight row
+// (fetched ahead by the group in which the run ends), or the span's head / tail scratch row when
+// the run crosses the span's border.  Plain SGD on summed rows of float4 columns that fit one
+// pass over the lanes of a group; everything else runs in the first form.
+template <int LPR, int NB> __global__ __launch_bounds__(256) void bwd_reduce_walk_kernel(BwdArgs a)
 {
+    typedef float4 V;
     constexpr int G = FAE_WAVE / LPR;
-    constexpr int VW = sizeof(V) / sizeof(float);
-    const int sid = blockIdx.x * (256 / FAE_WAVE) + threadIdx.x / FAE_WAVE;
+    __shared__ __align__(16) int lk[256 / FAE_WAVE][BWD_SPAN_MAX + 4];
+    __shared__ __align__(16) int lv[256 / FAE_WAVE][BWD_SPAN_MAX];
+    const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x / FAE_WAVE);
+    const int sid = blockIdx.x * a.wg_waves + wv;
     if (sid >= a.n_spans)
         return;
     const SpanInfo sp = bwd_span_info(a, sid);
     const int lane = fae_lane(), g = lane / LPR, l = lane % LPR;
-    const int ncols = a.dim / VW;
+    const int ncols = a.dim / 4;
     const int n_hot = a.n_hot[sp.z];
     V *W = (V *)a.W[sp.z];
-    const float *gbase = a.gout + (int64_t)sp.z * a.dim;
+    const char *wb = (const char *)W;
+    const char *gb = (const char *)(a.gout + (int64_t)sp.z * a.dim);
     V *part = (V *)(a.partial + (int64_t)sid * 2 * a.dim);
-    const int share = a.span / G; // lookups per group (the span is a multiple of 64)
-    const int q0 = sp.pos0 + g * share < sp.pos1 ? sp.pos0 + g * share : sp.pos1;
-    const int q1 = q0 + share < sp.pos1 ? q0 + share : sp.pos1;
+    const int share = a.span / G; // lookups per group: a multiple of NB (the span is a multiple of 64)
+    const bool active = l < ncols;
+    const uint32_t colb = (uint32_t)l * sizeof(V);
+    const uint32_t rowb = (uint32_t)a.dim * sizeof(float);
+    const uint32_t gstrideb = (uint32_t)a.gout_stride * sizeof(float);
 
-    for (int c0 = 0; c0 < ncols; c0 += LPR) {
-        const int c = c0 + l;
-        const bool active = c < ncols;
-        // NB pairs of a batch and the key that follows them; KEY_NONE past the share's end
-        auto load_pairs = [&](int j0, int *kk, int *ss) {
-            if (NB % 4 == 0 && (j0 & 3) == 0 && j0 + NB <= q1) {
+    // the span's pairs; past its end a key that matches no slot and sample 0 (a row that exists)
+    {
+        constexpr int T = BWD_SPAN_MAX / FAE_WAVE;
+        int fk[T], fv[T];
 #pragma unroll
-                for (int u = 0; u < NB; u += 4) {
-                    const int4 k4 = *(const int4 *)(a.keys_in + j0 + u);
-                    const int4 s4 = *(const int4 *)(a.vals_in + j0 + u);
-                    kk[u] = k4.x; kk[u + 1] = k4.y; kk[u + 2] = k4.z; kk[u + 3] = k4.w;
-                    ss[u] = s4.x; ss[u + 1] = s4.y; ss[u + 2] = s4.z; ss[u + 3] = s4.w;
-                }
-            } else {
+        for (int t = 0; t < T; ++t) { // every load is issued before the first store (indices clamped into the span)
+            const int p = sp.pos0 + t * FAE_WAVE + lane;
+            const int pc = p < sp.pos1 ? p : sp.pos1 - 1;
+            fk[t] = a.keys_in[pc];
+            fv[t] = a.vals_in[pc];
+        }
 #pragma unroll
-                for (int u = 0; u < NB; ++u) {
-                    kk[u] = j0 + u < q1 ? a.keys_in[j0 + u] : KEY_NONE;
-                    ss[u] = j0 + u < q1 ? a.vals_in[j0 + u] : 0;
-                }
+        for (int t = 0; t < T; ++t) {
+            const int i = t * FAE_WAVE + lane;
+            const bool in = sp.pos0 + i < sp.pos1;
+            if (i < a.span) {
+                lk[wv][i] = in ? fk[t] : KEY_NONE;
+                lv[wv][i] = in ? fv[t] : 0;
             }
-            kk[NB] = j0 + NB < q1 ? a.keys_in[j0 + NB] : KEY_NONE;
-        };
-        int cur = KEY_NONE;  // key of the run being summed
-        V acc = bwd_vec<V>::zero();
-        int hk = KEY_NONE;   // the share's first run, once it has closed inside the share
-        V hv = bwd_vec<V>::zero();
-        bool multi = false;  // a run has closed inside the share
-        bool multi_ahead = false; // the same, as of the batch whose loads are being issued
-        int kn[NB + 1], sn[NB];
-        load_pairs(q0, kn, sn);
-        for (int j0 = q0; j0 < q1; j0 += NB) {
+        }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    const int *mk = lk[wv] + g * share;
+    const int *mv = lv[wv] + g * share;
+
+    // Weight rows of the share's first and last run, for whichever joined run ends there (the pass
+    // over the groups below).  Their slots are the share's first and last key; no lane of the
+    // launch writes these rows before that pass, so they can be fetched ahead of everything else.
+    V wh = bwd_vec<V>::zero(), wt = bwd_vec<V>::zero();
+    if (active) {
+        const int k0 = mk[0], k1 = mk[share - 1];
+        if (k0 < n_hot)
+            wh = *(const V *)(wb + (__umul24((uint32_t)k0, rowb) + colb));
+        if (k1 < n_hot)
+            wt = *(const V *)(wb + (__umul24((uint32_t)k1, rowb) + colb));
+    }
+    int cur = KEY_NONE; // key of the run being summed
+    V acc = bwd_vec<V>::zero();
+    int hk = KEY_NONE;  // the share's first run, once it has closed inside the share
+    V hv = bwd_vec<V>::zero();
+    bool multi = false;       // a run has closed inside the share
+    bool multi_ahead = false; // the same, as of the batch whose loads are being issued
+    if (active) {
+        for (int j = 0; j < share; j += NB) {
             int kk[NB + 1], ss[NB];
 #pragma unroll
-            for (int u = 0; u < NB; ++u) {
-                kk[u] = kn[u];
-                ss[u] = sn[u];
+            for (int u = 0; u < NB; u += 4) {
+                const int4 k4 = *(const int4 *)(mk + j + u);
+                const int4 s4 = *(const int4 *)(mv + j + u);
+                kk[u] = k4.x; kk[u + 1] = k4.y; kk[u + 2] = k4.z; kk[u + 3] = k4.w;
+                ss[u] = s4.x; ss[u + 1] = s4.y; ss[u + 2] = s4.z; ss[u + 3] = s4.w;
             }
-            kk[NB] = kn[NB];
+            // the share's last lookup never closes its run here: the pass over the groups below does
+            kk[NB] = j + NB < share ? mk[j + NB] : kk[NB - 1];
             V vv[NB], ww[NB];
             bool closes[NB];
-            if (j0 + NB <= q1 && active) {
-                // a full batch: every load is issued without a branch around it (a lookup that needs no
-                // weight row reads row 0 of the table, a line that stays in the cache), and the
-                // running sums are kept with selects instead of branches
-#pragma unroll
-                for (int u = 0; u < NB; ++u) {
-                    vv[u] = ((const V *)(gbase + (int64_t)ss[u] * a.gout_stride))[c];
-                    closes[u] = kk[u + 1] != KEY_NONE && kk[u + 1] != kk[u];
-                    const bool need_w = closes[u] && multi_ahead && kk[u] < n_hot;
-                    ww[u] = W[(int64_t)(need_w ? kk[u] : 0) * ncols + c];
-                    multi_ahead = multi_ahead || closes[u];
-                }
-                load_pairs(j0 + NB, kn, sn);
-#pragma unroll
-                for (int u = 0; u < NB; ++u) {
-                    const bool same = kk[u] == cur;
-                    V t = vv[u];
-                    if (same)
-                        bwd_vec<V>::add(t, acc);
-                    acc = t;
-                    cur = kk[u];
-                    const bool first_close = closes[u] && !multi;
-                    if (first_close) {
-                        hk = cur;
-                        hv = acc;
-                    }
-                    if (closes[u] && multi && cur < n_hot)
-                        W[(int64_t)cur * ncols + c] = bwd_vec<V>::sgd(ww[u], acc, a.lr);
-                    multi = multi || closes[u];
-                }
-                continue;
-            }
 #pragma unroll
             for (int u = 0; u < NB; ++u) {
-                vv[u] = (active && kk[u] != KEY_NONE) ? ((const V *)(gbase + (int64_t)ss[u] * a.gout_stride))[c]
-                                                     : bwd_vec<V>::zero();
-                // a run closes here if another key follows inside the share
-                closes[u] = kk[u] != KEY_NONE && kk[u + 1] != KEY_NONE && kk[u + 1] != kk[u];
-                const bool need_w = closes[u] && multi_ahead && active && kk[u] < n_hot;
-                ww[u] = need_w ? W[(int64_t)kk[u] * ncols + c] : bwd_vec<V>::zero();
+                vv[u] = *(const V *)(gb + (__umul24((uint32_t)ss[u], gstrideb) + colb));
+                closes[u] = kk[u + 1] != kk[u];
+                if (closes[u] && multi_ahead && kk[u] < n_hot) // read under the same condition below
+                    ww[u] = *(const V *)(wb + (__umul24((uint32_t)kk[u], rowb) + colb));
                 multi_ahead = multi_ahead || closes[u];
             }
-            load_pairs(j0 + NB, kn, sn); // past the share's end it loads nothing
 #pragma unroll
             for (int u = 0; u < NB; ++u) {
-                const int k = kk[u];
-                if (k == KEY_NONE)
-                    continue;
-                if (k == cur) {
-                    bwd_vec<V>::add(acc, vv[u]);
-                } else {
-                    cur = k;
-                    acc = vv[u];
-                }
+                const bool same = kk[u] == cur;
+                acc.x = (same ? acc.x : 0.f) + vv[u].x;
+                acc.y = (same ? acc.y : 0.f) + vv[u].y;
+                acc.z = (same ? acc.z : 0.f) + vv[u].z;
+                acc.w = (same ? acc.w : 0.f) + vv[u].w;
+                cur = kk[u];
                 if (closes[u]) {
                     if (!multi) {
                         hk = cur;
                         hv = acc;
-                        multi = true;
-                    } else if (active && cur < n_hot) {
-                        W[(int64_t)cur * ncols + c] = bwd_vec<V>::sgd(ww[u], acc, a.lr);
+                    } else if (cur < n_hot) {
+                        *(V *)(const_cast<char *>(wb) + (__umul24((uint32_t)cur, rowb) + colb)) =
+                            bwd_vec<V>::sgd(ww[u], acc, a.lr);
                     }
+                    multi = true;
                 }
             }
         }
-        // weight rows of the group's first and last run, for whichever joined run ends there
-        const V wh = (multi && active && hk < n_hot) ? W[(int64_t)hk * ncols + c] : bwd_vec<V>::zero();
-        const V wt = (cur != KEY_NONE && active && cur < n_hot) ? W[(int64_t)cur * ncols + c] : bwd_vec<V>::zero();
-        // a joined run with key k and sum v that ends in group `at` (as its first run if head)
-        auto flush = [&](int at, bool head, int k, const V &v) {
-            if (g != at || !active || k >= n_hot)
-                return;
-            if (sp.head_open && k == sp.first_key)
-                part[c] = v;
-            else if (sp.tail_open && k == sp.last_key)
-                part[ncols + c] = v;
-            else
-                W[(int64_t)k * ncols + c] = bwd_vec<V>::sgd(head ? wh : wt, v, a.lr);
-        };
-        int ck = KEY_NONE, gprev = 0;
-        V cv = bwd_vec<V>::zero();
-#pragma unroll
-        for (int gp = 0; gp < G; ++gp) {
-            const int e_tk = __builtin_amdgcn_readlane(cur, gp * LPR);
-            if (e_tk == KEY_NONE)
-                continue; // an empty share (only past the span's end)
-            const int e_multi = __builtin_amdgcn_readlane((int)multi, gp * LPR);
-            const int e_hk = __builtin_amdgcn_readlane(hk, gp * LPR);
-            const V e_tv = bwd_shfl<V>(acc, gp * LPR + l);
-            const V e_hv = bwd_shfl<V>(hv, gp * LPR + l);
-            const int fk = e_multi ? e_hk : e_tk; // key of the share's first run
-            V first = e_multi ? e_hv : e_tv;
-            if (fk == ck)
-                bwd_vec<V>::add(first, cv); // continues the run carried over from the shares before
-            else if (ck != KEY_NONE)
-                flush(gprev, false, ck, cv);
-            if (e_multi) {
-                flush(gp, true, fk, first);
-                ck = e_tk;
-                cv = e_tv;
-            } else {
-                ck = fk;
-                cv = first;
-            }
-            gprev = gp;
-        }
-        if (ck != KEY_NONE)
-            flush(gprev, false, ck, cv);
     }
+    // a joined run with key k and sum v that ends in group `at` (as its first run if head)
+    const int c = l;
+    auto flush = [&](int at, bool head, int k, const V &v) {
+        if (g != at || !active || k >= n_hot)
+            return;
+        if (sp.head_open && k == sp.first_key) {
+            if (a.fused_fixup)
+                bwd_store_shared(&part[c], v);
+            else
+                part[c] = v;
+        } else if (sp.tail_open && k == sp.last_key) {
+            if (a.fused_fixup)
+                bwd_store_shared(&part[ncols + c], v);
+            else
+                part[ncols + c] = v;
+        } else {
+            W[(int64_t)k * ncols + c] = bwd_vec<V>::sgd(head ? wh : wt, v, a.lr);
+        }
+    };
+    int ck = KEY_NONE, gprev = 0;
+    V cv = bwd_vec<V>::zero();
+#pragma unroll
+    for (int gp = 0; gp < G; ++gp) {
+        const int e_tk = __builtin_amdgcn_readlane(cur, gp * LPR);
+        const int e_multi = __builtin_amdgcn_readlane((int)multi, gp * LPR);
+        if (e_tk == KEY_NONE && !e_multi)
+            continue; // a share that lies past the span's end
+        const int e_hk = __builtin_amdgcn_readlane(hk, gp * LPR);
+        const V e_tv = bwd_shfl<V>(acc, gp * LPR + l);
+        const V e_hv = bwd_shfl<V>(hv, gp * LPR + l);
+        const int fk = e_multi ? e_hk : e_tk; // key of the share's first run
+        V first = e_multi ? e_hv : e_tv;
+        if (fk == ck)
+            bwd_vec<V>::add(first, cv); // continues the run carried over from the shares before
+        else if (ck != KEY_NONE)
+            flush(gprev, false, ck, cv);
+        if (e_multi) {
+            flush(gp, true, fk, first);
+            ck = e_tk; // no key (the span ends inside this share): nothing is carried on
+            cv = e_tv;
+        } else {
+            ck = fk;
+            cv = first;
+        }
+        gprev = gp;
+    }
+    if (ck != KEY_NONE)
+        flush(gprev, false, ck, cv);
+    if (a.fused_fixup)
+        bwd_finish_borders<V, LPR>(a, sp, sid, n_hot, W, part, ncols);
 }
 
 // one wave per span: if a run starts in this span and continues past its end, add the
@@ -656,17 +663,26 @@ __global__ __launch_bounds__(256) void dbg_runlen_kernel(BwdArgs a)
 // host side
 // ---------------------------------------------------------------------------------
 namespace {
+// the second form exists for float4 columns on 4 to 64 lanes per row (the host asks for no other)
+template <typename V, int LPR> void launch_walk(fae_ctx *ctx, const BwdArgs &a, dim3 grid, dim3 block)
+{
+    if constexpr (sizeof(V) == sizeof(float4) && LPR >= 4) {
+        if (ctx->opt_unroll != 4 && a.span / (FAE_WAVE / LPR) >= 8)
+            hipLaunchKernelGGL((bwd_reduce_walk_kernel<LPR, 8>), grid, block, 0, ctx->stream, a);
+        else
+            hipLaunchKernelGGL((bwd_reduce_walk_kernel<LPR, 4>), grid, block, 0, ctx->stream, a);
+    }
+}
+
 template <typename V, int LPR> void launch_reduce(fae_ctx *ctx, const BwdArgs &a)
 {
     {
         fae_ktimer kt(ctx, FAE_K_BWD_REDUCE);
-        const dim3 grid((a.n_spans + 3) / 4);
-        if (ctx->opt_reduce != 2 || a.mean || a.adagrad) // the variants exist in the scan form only
-            hipLaunchKernelGGL((bwd_reduce_kernel<V, LPR>), grid, dim3(256), 0, ctx->stream, a);
-        else if (ctx->opt_unroll == 8)
-            hipLaunchKernelGGL((bwd_reduce_walk_kernel<V, LPR, 8>), grid, dim3(256), 0, ctx->stream, a);
+        const dim3 grid((a.n_spans + a.wg_waves - 1) / a.wg_waves), block(a.wg_waves * FAE_WAVE);
+        if (a.form == 1)
+            launch_walk<V, LPR>(ctx, a, grid, block);
         else
-            hipLaunchKernelGGL((bwd_reduce_walk_kernel<V, LPR, 4>), grid, dim3(256), 0, ctx->stream, a);
+            hipLaunchKernelGGL((bwd_reduce_kernel<V, LPR>), grid, block, 0, ctx->stream, a);
     }
     if (a.fused_fixup)
         return;

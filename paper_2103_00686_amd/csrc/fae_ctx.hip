@@ -221,6 +221,8 @@ extern "C" int32_t fae_set_option(fae_ctx *ctx, const char *name, int64_t value)
         ctx->opt_fixup = value;
     else if (!strcmp(name, "reduce_variant") && value >= 0 && value <= 2)
         ctx->opt_reduce = value;
+    else if (!strcmp(name, "reduce_wg_waves") && (value == 0 || value == 1 || value == 2 || value == 4))
+        ctx->opt_wg_waves = value;
     else if (!strcmp(name, "reduce_unroll") && (value == 0 || value == 4 || value == 8))
         ctx->opt_unroll = value;
     else

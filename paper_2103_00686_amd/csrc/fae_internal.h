@@ -40,6 +40,7 @@ struct fae_ctx {
     int64_t opt_span = 0;       // lookups per wave in the reduce kernel (0 = auto)
     int64_t opt_fixup = 0;      // runs that cross span borders: 0 auto (inside the reduce kernel), 1 separate kernel
     int64_t opt_reduce = 0;     // reduce kernel: 0 auto, 1 scan across lane groups, 2 a share of the span per lane group
+    int64_t opt_wg_waves = 0;   // reduce kernel: waves per workgroup (0 = auto, 1, 2, 4)
     int64_t opt_unroll = 0;     // gradient rows in flight per lane group in the second form (0 = auto, 4, 8)
     char err[512] = {0};
     // side stream for work that may overlap the main stream (backward presort)

@@ -49,7 +49,7 @@ def test_workload_end_to_end(dev, cfg_id, materialise):
 @pytest.mark.parametrize("reduce_variant,unroll,span,fixup", [(1, 0, 0, 0), (1, 0, 64, 0), (1, 0, 256, 0), (1, 0, 0, 1), (2, 0, 0, 0),
                                                               (2, 4, 64, 0), (2, 8, 256, 0), (2, 8, 128, 1)])
 def test_reduce_variants(dev, cfg_id, reduce_variant, unroll, span, fixup):
-    """Both forms of the segment reduce, every load depth and span length, border-crossing runs
+    """All forms of the segment reduce, every load depth and span length, border-crossing runs
     finished inside the kernel or by the fix-up kernel, on one-hot and multi-hot workloads; two
     steps, so the second sees rows the first has changed."""
     w = S.workload(cfg_id, "test")
@@ -66,6 +66,22 @@ def test_reduce_variants(dev, cfg_id, reduce_variant, unroll, span, fixup):
     p.check_forward(batches[0], exact_gather=False)
 
 
+@pytest.mark.parametrize("reduce_variant", [1, 2])
+@pytest.mark.parametrize("wg_waves", [2, 4])
+def test_reduce_workgroup_sizes(dev, reduce_variant, wg_waves):
+    """The reduce kernel with two and four spans per workgroup (one is the default)."""
+    w = S.workload(3, "test")
+    p = T.Pipeline(w, dev, profile_chunks=1)
+    B.fae_set_option(p.hp.ctx, "reduce_variant", reduce_variant)
+    B.fae_set_option(p.hp.ctx, "reduce_wg_waves", wg_waves)
+    p.check_profile()
+    p.check_cutoff()
+    p.check_build()
+    batches = T.hot_batches(p, 2)
+    p.check_backward(batches[0], stream=32)
+    p.check_backward(batches[-1], stream=33)
+
+
 @pytest.mark.parametrize("variant", [1, 2])
 def test_profile_variants_agree_with_oracle(dev, variant):
     w = S.workload(2, "test")
@@ -75,7 +91,7 @@ def test_profile_variants_agree_with_oracle(dev, variant):
 
 
 @pytest.mark.parametrize("variant", [1, 2])
-@pytest.mark.parametrize("dim", [4, 20, 32, 128, 6, 1, 260])
+@pytest.mark.parametrize("dim", [4, 16, 20, 32, 128, 6, 1, 260])
 def test_forward_backward_shapes(dev, variant, dim):
     """Both lane mappings, vector and scalar paths, dims that are not powers of two, bags of
     length 0..70 with repeats."""
@@ -83,7 +99,7 @@ def test_forward_backward_shapes(dev, variant, dim):
     n_hot, S_ = [700, 3, 1], 333
     hp = HotPath(n_hot, dim, 0)
     B.fae_set_option(hp.ctx, "fwd_variant", variant)
-    B.fae_set_option(hp.ctx, "reduce_variant", variant)     # both forms of the segment reduce see every shape
+    B.fae_set_option(hp.ctx, "reduce_variant", variant)     # every form of the segment reduce sees every shape
     hp.n_hot = n_hot
     Wref = [(rng.random((n, dim), dtype=np.float32) - 0.5) for n in n_hot]
     hp.hotW = [torch.from_numpy(x).to(dev) for x in Wref]
@@ -122,7 +138,7 @@ def test_forward_backward_shapes(dev, variant, dim):
 @pytest.mark.parametrize("S_,sort_variant,reduce_variant,span,fixup",
                          [(50_000, 0, 1, 0, 0), (50_000, 0, 1, 64, 0), (50_000, 0, 1, 256, 1), (50_000, 1, 2, 0, 0),
                           (50_000, 3, 2, 0, 0), (300_000, 0, 2, 0, 0), (300_000, 1, 1, 64, 0), (300_000, 3, 1, 0, 1), (300_000, 4, 1, 0, 0),
-                          (50_000, 0, 2, 0, 0)])
+                          (50_000, 0, 2, 0, 0), (300_000, 0, 2, 64, 1), (300_000, 3, 2, 256, 0)])
 def test_backward_long_runs_and_many_tiles(dev, S_, sort_variant, reduce_variant, span, fixup):
     """One slot repeated tens of thousands of times (a run that crosses hundreds of spans and, in
     the key-range sort, a single value larger than the LDS buffers), runs of about two spans,
