@@ -207,61 +207,64 @@ __device__ __forceinline__ void lds_sort_block(const int32_t *slots, const int32
                                                int pshift, int n_samples, int32_t *keys_out, int32_t *vals_out,
                                                uint32_t *status)
 {
-    __shared__ int keyA[LSORT_MAX];
+    __shared__ __align__(16) int keyA[LSORT_MAX];
     __shared__ unsigned short perm[2][LSORT_MAX];
     __shared__ int wcnt[LSORT_WAVES][RADIX];
     __shared__ int scan_lds[LSORT_THREADS / FAE_WAVE + 1];
     const int w = threadIdx.x / FAE_WAVE, lane = fae_lane();
-    const uint64_t lt_mask = (1ull << lane) - 1ull;
 
-    // load every key of the table; count the keys of lower parts (they precede this part's output)
-    bool bad = false;
-    int below = 0;
-    {
-        int kk[LSORT_MAX / LSORT_THREADS];
+    // Every key of the table, sixteen consecutive lookups per thread: the keys go to LDS (the
+    // passes below fetch them by position) and stay in registers for the ordered selection of
+    // this part's lookups, which then needs no sweep over LDS: a thread's selected positions
+    // follow those of all threads before it.
+    constexpr int PER = LSORT_MAX / LSORT_THREADS;
+    int kk[PER];
+    const int e0 = threadIdx.x * PER;
+    if (e0 + PER <= n && (((uintptr_t)slots) & 15) == 0) {
 #pragma unroll
-        for (int i = 0; i < LSORT_MAX / LSORT_THREADS; ++i) { // all loads in flight before the first use
-            const int e = threadIdx.x + i * LSORT_THREADS;
-            kk[i] = e < n ? slots[e] : 0;
+        for (int i = 0; i < PER; i += 4) {
+            const int4 t = *(const int4 *)(slots + e0 + i);
+            kk[i] = t.x; kk[i + 1] = t.y; kk[i + 2] = t.z; kk[i + 3] = t.w;
         }
+    } else {
 #pragma unroll
-        for (int i = 0; i < LSORT_MAX / LSORT_THREADS; ++i) {
-            const int e = threadIdx.x + i * LSORT_THREADS;
-            if (e < n) {
-                int k = kk[i];
-                if ((unsigned)k >= (unsigned)n_hot) {
-                    bad = true;
-                    k = n_hot; // behind every valid slot; never dereferenced
-                }
-                keyA[e] = k;
-                below += (k >> pshift) < part ? 1 : 0;
+        for (int i = 0; i < PER; ++i)
+            kk[i] = e0 + i < n ? slots[e0 + i] : 0;
+    }
+    bool bad = false;
+    int below = 0, mine = 0; // this thread's keys in lower parts (they precede this part's output) / in this part
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+        if (e0 + i < n) {
+            if ((unsigned)kk[i] >= (unsigned)n_hot) {
+                bad = true;
+                kk[i] = n_hot; // behind every valid slot; never dereferenced
             }
+            const int pk = kk[i] >> pshift;
+            below += pk < part ? 1 : 0;
+            mine += pk == part ? 1 : 0;
+        } else {
+            kk[i] = -1; // in no part
         }
     }
+#pragma unroll
+    for (int i = 0; i < PER; i += 4)
+        if (e0 + i < n) // keyA is a multiple of four keys long, so a ragged end may write past n
+            *(int4 *)(keyA + e0 + i) = make_int4(kk[i], kk[i + 1], kk[i + 2], kk[i + 3]);
     if (bad && part == 0)
         fae_flag(status, FAE_STATUS_ERANGE);
-    // ordered selection of this part's lookups: wave w scans positions [w*per, (w+1)*per)
-    const int per = ((n + LSORT_THREADS - 1) / LSORT_THREADS) * FAE_WAVE;
-    __syncthreads();
-    int mine = 0;
-    for (int i = 0; i < per; i += FAE_WAVE) {
-        const int e = w * per + i + lane;
-        mine += (e < n && (keyA[e] >> pshift) == part) ? 1 : 0;
-    }
+    // one scan for both counts (each at most LSORT_MAX = 2^14)
     int n_below, n_sel;
-    (void)fae_block_excl_scan<LSORT_THREADS>(below, scan_lds, &n_below);
     {
-        // per-wave totals -> exclusive prefix over the waves (scan over threads, read at lane 0)
-        const int ex = fae_block_excl_scan<LSORT_THREADS>(mine, scan_lds, &n_sel);
-        int run = __shfl(ex, 0, FAE_WAVE);
-        for (int i = 0; i < per; i += FAE_WAVE) {
-            const int e = w * per + i + lane;
-            const bool sel = e < n && (keyA[e] >> pshift) == part;
-            const uint64_t m = __ballot(sel);
-            if (sel)
-                perm[0][run + __popcll(m & lt_mask)] = (unsigned short)e;
-            run += __popcll(m);
-        }
+        int both;
+        const int ex = fae_block_excl_scan<LSORT_THREADS>((below << 16) | mine, scan_lds, &both);
+        n_below = both >> 16;
+        n_sel = both & 0xffff;
+        int at = ex & 0xffff;
+#pragma unroll
+        for (int i = 0; i < PER; ++i)
+            if (kk[i] >= 0 && (kk[i] >> pshift) == part)
+                perm[0][at++] = (unsigned short)(e0 + i);
     }
     __syncthreads();
 
