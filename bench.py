@@ -43,10 +43,14 @@ def main():
     ap.add_argument("--set", action="append", default=[], help="library option name=value (ablation)")
     ap.add_argument("--graph", action="store_true",
                     help="capture each step into a HIP graph and time the replays (same kernels, fewer launches)")
-    ap.add_argument("--presort", choices=["fused", "side", "none"], default="fused",
+    ap.add_argument("--presort", choices=["fused", "side", "none", "ahead"], default="fused",
                     help="where the backward's sort runs: in the forward's launch (default, where the shape "
-                         "allows), on the side stream, or inside fae_embbag_bwd_sgd")
+                         "allows), on the side stream, inside fae_embbag_bwd_sgd, or one step ahead on the side "
+                         "stream (the next batch's sort beside this batch's forward and backward)")
     args = ap.parse_args()
+    if args.graph and args.presort == "ahead":
+        print("bench.py: --graph captures one stream; --presort ahead uses two", file=sys.stderr)
+        sys.exit(2)
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
         sys.exit(2)
@@ -163,7 +167,10 @@ def run_workload(args, cfg_id, n_steps, n_warmup, with_cpu):
     outs = [torch.empty((hb.n_samples, nt, D), dtype=torch.float32, device=dev) for hb in batches]
     ws_need = max(B.fae_bwd_workspace_bytes(hp.hot_tables, hb.n_samples, hb.n_lookups) for hb in batches)
     hp._workspace("bwd", ws_need)
-    steps_fn = [hp.prepare_step(hb, g, o, w.lr, presort=args.presort) for hb, g, o in zip(batches, gouts, outs)]
+    if args.presort == "ahead":
+        steps_fn = hp.prepare_pipeline(batches, gouts, outs, w.lr)
+    else:
+        steps_fn = [hp.prepare_step(hb, g, o, w.lr, presort=args.presort) for hb, g, o in zip(batches, gouts, outs)]
 
     # accounting per batch: lookups, bags, distinct rows
     acct = []

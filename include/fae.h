@@ -227,8 +227,11 @@ size_t fae_bwd_workspace_bytes(const fae_tables *hot_tables, int64_t n_samples,
  * main stream between this call and fae_embbag_bwd_sgd (the forward, the dense layers).
  * It starts after all work queued on the main stream so far.  A following
  * fae_embbag_bwd_sgd with the same batch and workspace waits for it and skips its own
- * sort; with any other batch or workspace it waits and sorts itself.  The batch and the
- * workspace must stay untouched in between.  Asynchronous. */
+ * sort; with another batch in that workspace it waits and sorts itself.  The batch and the
+ * workspace must stay untouched in between.  Sorted pairs are remembered per workspace, for
+ * up to four workspaces at a time (beyond that the oldest are forgotten and their backward
+ * call sorts again), so the next batch can be sorted into a second workspace while this
+ * batch's forward and backward still run.  Asynchronous. */
 int32_t fae_embbag_bwd_presort(fae_ctx *ctx, const fae_tables *hot_tables, const fae_batch *hot_batch,
                                void *ws, size_t ws_bytes);
 /* fae_embbag_fwd that also carries the sort of the backward for the same batch: when every

@@ -241,19 +241,21 @@ static int32_t bwd_impl(fae_ctx *ctx, const fae_tables *hot_tables, float *const
 
     // 1 + 2. sorted (slot, sample) pairs: take them from a matching presort, or sort now
     int cur = 0;
-    if (ctx->presort.valid && ctx->presort.side) {
-        // whatever the side stream was asked to do must be finished before this workspace is used
-        FAE_HIP(ctx, hipStreamWaitEvent(ctx->stream, ctx->ev_join, 0));
+    fae_ctx::Presort *ps = ctx->presort_find(ws);
+    if (ps && ps->side) {
+        // whatever the side stream was asked to do in this workspace must be finished before it is used
+        FAE_HIP(ctx, hipStreamWaitEvent(ctx->stream, ps->ev_join, 0));
     }
-    if (ctx->presort.valid && ctx->presort.ws == ws && ctx->presort.first_indices == hot_batch->h_indices[0] &&
-        ctx->presort.n_samples == hot_batch->n_samples && ctx->presort.n_lookups == plan.N) {
-        cur = ctx->presort.cur;
+    if (ps && ps->first_indices == hot_batch->h_indices[0] && ps->n_samples == hot_batch->n_samples &&
+        ps->n_lookups == plan.N) {
+        cur = ps->cur;
     } else {
         rc = bwd_sort_stage(ctx, ctx->stream, hot_tables, hot_batch, su, &cur);
         if (rc != FAE_OK)
             return rc;
     }
-    ctx->presort.valid = false;
+    if (ps)
+        ps->valid = false;
     a.keys_in = w.keys[cur];
     a.vals_in = w.vals[cur];
     a.keys_out = nullptr;

@@ -577,10 +577,13 @@ extern "C" int32_t fae_embbag_bwd_presort(fae_ctx *ctx, const fae_tables *hot_ta
     int32_t rc = bwd_setup(ctx, hot_tables, hot_batch, ws, ws_bytes, "fae_embbag_bwd_presort", &su);
     if (rc != FAE_OK)
         return rc;
-    ctx->presort.valid = false;
+    FAE_HIP(ctx, hipSetDevice(ctx->device));
+    fae_ctx::Presort *ps = ctx->presort_slot(ws);
+    if (ps->valid && ps->side) // an unused sort (of this workspace, or the oldest one): nothing else would wait for it
+        FAE_HIP(ctx, hipStreamWaitEvent(ctx->stream, ps->ev_join, 0));
+    ps->valid = false;
     if (su.empty)
         return FAE_OK;
-    FAE_HIP(ctx, hipSetDevice(ctx->device));
     // fork: the side stream starts after everything already queued on the main stream
     // (earlier users of this workspace, producers of the slots)
     FAE_HIP(ctx, hipEventRecord(ctx->ev_fork, ctx->stream));
@@ -589,14 +592,15 @@ extern "C" int32_t fae_embbag_bwd_presort(fae_ctx *ctx, const fae_tables *hot_ta
     rc = bwd_sort_stage(ctx, ctx->aux_stream, hot_tables, hot_batch, su, &cur);
     if (rc != FAE_OK)
         return rc;
-    FAE_HIP(ctx, hipEventRecord(ctx->ev_join, ctx->aux_stream));
-    ctx->presort.valid = true;
-    ctx->presort.side = true;
-    ctx->presort.ws = ws;
-    ctx->presort.first_indices = hot_batch->h_indices[0];
-    ctx->presort.n_samples = hot_batch->n_samples;
-    ctx->presort.n_lookups = su.plan.N;
-    ctx->presort.cur = cur;
+    FAE_HIP(ctx, hipEventRecord(ps->ev_join, ctx->aux_stream));
+    ps->valid = true;
+    ps->side = true;
+    ps->ws = ws;
+    ps->first_indices = hot_batch->h_indices[0];
+    ps->n_samples = hot_batch->n_samples;
+    ps->n_lookups = su.plan.N;
+    ps->cur = cur;
+    ps->age = ++ctx->presort_clock;
     return FAE_OK;
 }
 
@@ -666,6 +670,10 @@ extern "C" int32_t fae_embbag_fwd_presort(fae_ctx *ctx, const fae_tables *hot_ta
     if (!fused)
         return fae_embbag_fwd(ctx, hot_tables, h_hotW, hot_batch, out, out_row_stride);
     FAE_HIP(ctx, hipSetDevice(ctx->device));
+    fae_ctx::Presort *ps = ctx->presort_slot(ws);
+    if (ps->valid && ps->side) // an unused sort (of this workspace, or the oldest one): nothing else would wait for it
+        FAE_HIP(ctx, hipStreamWaitEvent(ctx->stream, ps->ev_join, 0));
+    ps->valid = false;
     FusedArgs f;
     memset(&f, 0, sizeof(f));
     bool in_lds[FAE_MAX_TABLES];
@@ -708,12 +716,13 @@ extern "C" int32_t fae_embbag_fwd_presort(fae_ctx *ctx, const fae_tables *hot_ta
         }
         FAE_LAUNCH_CHECK(ctx);
     }
-    ctx->presort.valid = true;
-    ctx->presort.side = false;
-    ctx->presort.ws = ws;
-    ctx->presort.first_indices = hot_batch->h_indices[0];
-    ctx->presort.n_samples = hot_batch->n_samples;
-    ctx->presort.n_lookups = su.plan.N;
-    ctx->presort.cur = 0;
+    ps->valid = true;
+    ps->side = false;
+    ps->ws = ws;
+    ps->first_indices = hot_batch->h_indices[0];
+    ps->n_samples = hot_batch->n_samples;
+    ps->n_lookups = su.plan.N;
+    ps->cur = 0;
+    ps->age = ++ctx->presort_clock;
     return FAE_OK;
 }

@@ -24,6 +24,14 @@ __global__ void fae_clear_words_kernel(uint32_t *p, int n)
         p[i] = 0u;
 }
 
+static bool fae_make_join_events(fae_ctx *ctx)
+{
+    for (auto &e : ctx->presort)
+        if (hipEventCreateWithFlags(&e.ev_join, hipEventDisableTiming) != hipSuccess)
+            return false;
+    return true;
+}
+
 extern "C" int32_t fae_create(fae_ctx **out, int32_t device, void *hip_stream)
 {
     if (!out)
@@ -60,7 +68,7 @@ extern "C" int32_t fae_create(fae_ctx **out, int32_t device, void *hip_stream)
     memset(ctx->h_block, 0, FAE_BLK_WORDS * sizeof(uint32_t));
     if (hipStreamCreateWithFlags(&ctx->aux_stream, hipStreamNonBlocking) != hipSuccess ||
         hipEventCreateWithFlags(&ctx->ev_fork, hipEventDisableTiming) != hipSuccess ||
-        hipEventCreateWithFlags(&ctx->ev_join, hipEventDisableTiming) != hipSuccess) {
+        !fae_make_join_events(ctx)) {
         (void)hipFree(ctx->d_block);
         (void)hipHostFree(ctx->h_block);
         delete ctx;
@@ -90,8 +98,9 @@ extern "C" void fae_destroy(fae_ctx *ctx)
     }
     if (ctx->ev_fork)
         (void)hipEventDestroy(ctx->ev_fork);
-    if (ctx->ev_join)
-        (void)hipEventDestroy(ctx->ev_join);
+    for (auto &e : ctx->presort)
+        if (e.ev_join)
+            (void)hipEventDestroy(e.ev_join);
     for (const fae_timed_launch &t : ctx->timed) {
         (void)hipEventDestroy(t.e0);
         (void)hipEventDestroy(t.e1);

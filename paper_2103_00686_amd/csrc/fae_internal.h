@@ -45,15 +45,41 @@ struct fae_ctx {
     char err[512] = {0};
     // side stream for work that may overlap the main stream (backward presort)
     hipStream_t aux_stream = nullptr;
-    hipEvent_t ev_fork = nullptr, ev_join = nullptr;
-    struct {
+    hipEvent_t ev_fork = nullptr;
+    // Sorted (slot, sample) pairs waiting for their backward call, one entry per workspace: a
+    // caller may sort the next batch (into a second workspace) while this one is still in use.
+    static constexpr int N_PRESORT = 4;
+    struct Presort {
         bool valid = false;
         bool side = false; // sorted on the side stream (needs the join event) or on the main stream
         const void *ws = nullptr;
         const void *first_indices = nullptr;
         int64_t n_samples = 0, n_lookups = 0;
         int cur = 0;
-    } presort;
+        uint64_t age = 0;
+        hipEvent_t ev_join = nullptr;
+    } presort[N_PRESORT];
+    uint64_t presort_clock = 0;
+    // the entry that holds (or will hold) the pairs in workspace ws: the one already bound to it,
+    // else a free one, else the oldest (whose owner then has to wait for it: see the callers)
+    Presort *presort_slot(const void *ws)
+    {
+        Presort *pick = &presort[0];
+        for (auto &e : presort) {
+            if (e.valid && e.ws == ws)
+                return &e;
+            if (pick->valid && (!e.valid || e.age < pick->age))
+                pick = &e;
+        }
+        return pick;
+    }
+    Presort *presort_find(const void *ws)
+    {
+        for (auto &e : presort)
+            if (e.valid && e.ws == ws)
+                return &e;
+        return nullptr;
+    }
     // per-kernel timing
     bool timing = false;
     std::vector<fae_timed_launch> timed;  // launches recorded since the last read

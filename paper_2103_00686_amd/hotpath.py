@@ -104,6 +104,49 @@ class HotPath:
         step._keep = keep
         return step
 
+    def prepare_pipeline(self, hbs: Sequence[HotBatch], gouts: Sequence[torch.Tensor], outs: Sequence[torch.Tensor],
+                         lr: float):
+        """Steps over a cycle of hot batches whose backward sorts run one step ahead: step i
+        starts the sort of batch i+1 on the side stream (into the other of two workspaces), then
+        runs forward and backward/SGD of batch i, whose pairs were sorted during step i-1.  Hot
+        mini-batches are formed ahead of training (Sec. 4), so the next batch is always known.
+        Returns one zero-argument callable per batch; they must be called in cyclic order."""
+        import ctypes as C
+        lib = B.load()
+        n = len(hbs)
+        need = max(B.fae_bwd_workspace_bytes(self.hot_tables, hb.n_samples, hb.n_lookups) for hb in hbs)
+        wss = [self._workspace(f"bwd_ahead{i}", need) for i in range(2)]
+        a_ws = [C.c_void_p(w.data_ptr()) for w in wss]
+        n_ws = [C.c_size_t(w.numel()) for w in wss]
+        t = self.hot_tables.c()
+        tr = C.byref(t)
+        wptr = B._ptrs(self.hotW, torch.float32)
+        stride, c_lr, h = C.c_int64(self.nt * self.dim), C.c_float(lr), self.ctx._h
+        bs = [hb.batch().c() for hb in hbs]
+        brs = [C.byref(b) for b in bs]
+        a_out = [C.c_void_p(o.data_ptr()) for o in outs]
+        a_gout = [C.c_void_p(g.data_ptr()) for g in gouts]
+        state = {"k": 0}
+        keep = (t, bs, wptr, wss, outs, gouts, hbs)
+
+        def make(i):
+            j = (i + 1) % n
+
+            def step():
+                k = state["k"]
+                cur, nxt = k & 1, (k + 1) & 1
+                rc = lib.fae_embbag_bwd_presort(h, tr, brs[j], a_ws[nxt], n_ws[nxt])
+                if rc == 0:
+                    rc = lib.fae_embbag_fwd(h, tr, wptr, brs[i], a_out[i], stride)
+                if rc == 0:
+                    rc = lib.fae_embbag_bwd_sgd(h, tr, wptr, brs[i], a_gout[i], stride, c_lr, None, a_ws[cur], n_ws[cur])
+                state["k"] = k + 1
+                if rc != 0:
+                    self.ctx.check(rc)
+            step._keep = keep
+            return step
+        return [make(i) for i in range(n)]
+
     # -- a1 -------------------------------------------------------------------------
     def profile(self, chunk: B.Batch):
         if self.counts is None:

@@ -184,6 +184,25 @@ class Pipeline:
                 self.wtol[z][uniq[z]] = (inherited + RTOL * mag[z]).astype(np.float32) * np.float32(1.001)
 
 
+    def check_step(self, hb: HotBatch, out: torch.Tensor, gout: torch.Tensor):
+        """After the library has run forward and backward/SGD of hb on its own (any call pattern):
+        the pooled output against the oracle's forward with the weights before the step, then the
+        updated rows against the oracle's update (which also advances the oracle's weights)."""
+        w = self.w
+        slots = [s.cpu().numpy() for s in hb.slots]
+        offs = [None if o is None else o.cpu().numpy() for o in hb.offsets]
+        ref, mag = O.embbag_fwd(self.hotW, hb.n_samples, slots, offs, want_mag=True)
+        inherited = O.embbag_fwd(self.wtol, hb.n_samples, slots, offs).astype(np.float64) * 1.001
+        assert_close_sum(out.cpu().numpy(), ref, mag, "forward", inherited)
+        uniq, runlen, mg = O.embbag_bwd_sgd(self.hotW, hb.n_samples, slots, offs, gout.cpu().numpy(), w.lr, want_mag=True)
+        for z in range(w.n_tables):
+            if uniq[z].size:
+                got = self.hp.hotW[z][:self.n_hot[z]].cpu().numpy()
+                inh = self.wtol[z][uniq[z]].astype(np.float64)
+                assert_close_sum(got[uniq[z]], self.hotW[z][uniq[z]], mg[z], f"updated rows of table {z}", inh)
+                self.wtol[z][uniq[z]] = (inh + RTOL * mg[z]).astype(np.float32) * np.float32(1.001)
+
+
 def hot_batches(p: Pipeline, n_batches: int, stream0: int = 10) -> List[HotBatch]:
     """Hot-only mini-batches of the workload's batch size, the way the workload makes them:
     conditional-hot draws for multi-hot workloads, partition of a mixed stream otherwise."""

@@ -66,6 +66,29 @@ def test_reduce_variants(dev, cfg_id, reduce_variant, unroll, span, fixup):
     p.check_forward(batches[0], exact_gather=False)
 
 
+@pytest.mark.parametrize("cfg_id,n_batches", [(2, 3), (3, 2), (4, 2)])
+def test_pipeline_sorts_one_step_ahead(dev, cfg_id, n_batches):
+    """Steps whose backward sort was started one step earlier on the side stream, into the other
+    of two workspaces; the first step finds nothing sorted and sorts itself, an odd cycle makes
+    the workspaces change roles from one pass over the batches to the next.  Output and weights
+    are checked after every step."""
+    w = S.workload(cfg_id, "test")
+    p = T.Pipeline(w, dev, profile_chunks=1)
+    p.check_profile()
+    p.check_cutoff()
+    p.check_build()
+    batches = T.hot_batches(p, n_batches)
+    gouts = [S.upstream_grads(w, 40 + i, hb.n_samples).to(dev) for i, hb in enumerate(batches)]
+    outs = [torch.zeros((hb.n_samples, w.n_tables, w.dim), dtype=torch.float32, device=dev) for hb in batches]
+    steps = p.hp.prepare_pipeline(batches, gouts, outs, w.lr)
+    n = len(batches)   # the partition of a mixed stream may form fewer hot batches than asked for
+    for k in range(2 * n + 1):
+        i = k % n
+        steps[i]()
+        p.hp.sync()
+        p.check_step(batches[i], outs[i], gouts[i])
+
+
 @pytest.mark.parametrize("reduce_variant", [1, 2])
 @pytest.mark.parametrize("wg_waves", [2, 4])
 def test_reduce_workgroup_sizes(dev, reduce_variant, wg_waves):
