@@ -148,9 +148,15 @@ class HotPath:
         return [make(i) for i in range(n)]
 
     # -- a1 -------------------------------------------------------------------------
+    def alloc_counts(self):
+        """Access counters of every table, zeroed (profile() makes them on first use otherwise)."""
+        self.counts = [torch.zeros(max(int(r), 1), dtype=torch.int32, device=self.dev) for r in self.tables.rows]
+        self.profiled_samples = 0
+        self.profiled_lookups = [0] * self.nt
+
     def profile(self, chunk: B.Batch):
         if self.counts is None:
-            self.counts = [torch.zeros(max(int(r), 1), dtype=torch.int32, device=self.dev) for r in self.tables.rows]
+            self.alloc_counts()
         B.fae_profile(self.ctx, self.tables, chunk, self.counts)
         self.profiled_samples += chunk.n_samples
         for z in range(self.nt):
