@@ -66,6 +66,45 @@ def test_reduce_variants(dev, cfg_id, reduce_variant, unroll, span, fixup):
     p.check_forward(batches[0], exact_gather=False)
 
 
+@pytest.mark.parametrize("cfg_id", [3, 4])
+def test_strict_relative_error_and_ulps(dev, cfg_id):
+    """Beside the must-pass bound |gpu - ref| <= 1e-5 * sum|terms|: how many elements also meet
+    the strict |gpu - ref| <= 1e-5 * |ref| (it is ill-defined only where a sum cancels), and,
+    for the record, the largest error in units of the reference's last place.  First step, so both sides start
+    from bit-identical weights."""
+    w = S.workload(cfg_id, "test")
+    p = T.Pipeline(w, dev, profile_chunks=1)
+    p.check_profile()
+    p.check_cutoff()
+    p.check_build()
+    hb = T.hot_batches(p, 1)[0]
+    slots = [s.cpu().numpy() for s in hb.slots]
+    offs = [None if o is None else o.cpu().numpy() for o in hb.offsets]
+    out = p.hp.forward(hb).cpu().numpy()
+    ref = O.embbag_fwd(p.hotW, hb.n_samples, slots, offs)
+    gout = S.upstream_grads(w, 77, hb.n_samples)
+    p.hp.backward_sgd(hb, gout.to(dev), w.lr)
+    p.hp.sync()
+    uniq, _ = O.embbag_bwd_sgd(p.hotW, hb.n_samples, slots, offs, gout.numpy(), w.lr)[:2]
+    pairs = [("forward", out, ref)]
+    for z in range(w.n_tables):
+        if uniq[z].size:
+            pairs.append((f"rows of table {z}", p.hp.hotW[z][:p.n_hot[z]].cpu().numpy()[uniq[z]], p.hotW[z][uniq[z]]))
+    n_all = n_strict = 0
+    worst_ulp = 0.0
+    for what, got, want in pairs:
+        err = np.abs(got.astype(np.float64) - want.astype(np.float64))
+        n_all += err.size
+        n_strict += int((err <= 1e-5 * np.abs(want.astype(np.float64))).sum())
+        ulp = np.spacing(np.abs(want.astype(np.float32))).astype(np.float64)
+        worst_ulp = max(worst_ulp, float((err / ulp).max()))
+    frac = n_strict / n_all
+    print(f"[strict] workload {cfg_id}: {frac:.6f} of {n_all} elements within 1e-5 relative; worst error {worst_ulp:.1f} ulp")
+    # the ulp figure is reported only: where addends of mixed sign cancel, the reference's last place
+    # is arbitrarily small against the rounding of the addends, which is what the must-pass bound uses
+    assert frac >= 0.999
+
+
 @pytest.mark.parametrize("cfg_id,n_batches", [(2, 3), (3, 2), (4, 2)])
 def test_pipeline_sorts_one_step_ahead(dev, cfg_id, n_batches):
     """Steps whose backward sort was started one step earlier on the side stream, into the other
