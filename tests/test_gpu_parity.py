@@ -128,6 +128,41 @@ def test_pipeline_sorts_one_step_ahead(dev, cfg_id, n_batches):
         p.check_step(batches[i], outs[i], gouts[i])
 
 
+def test_more_sorted_workspaces_than_the_library_remembers(dev):
+    """Six batches are sorted into six workspaces on the side stream before any backward runs;
+    the library remembers four, so the two oldest are forgotten (their backward calls wait for
+    the side stream and sort again).  Backward calls then run in an order of their own; every
+    update must be the oracle's."""
+    w = S.workload(2, "test")
+    p = T.Pipeline(w, dev, profile_chunks=1)
+    p.check_profile()
+    p.check_cutoff()
+    p.check_build()
+    base = T.hot_batches(p, 2)
+    # six batches from two: different samples (slices of different length), so every one differs
+    hbs = [b.slice(k, b.n_samples - 3 * k) for k, b in enumerate((base * 6)[:6])]
+    hbs = [HotBatch(h.n_samples, [x.clone() for x in h.slots], h.offsets, h.n_lookups) for h in hbs]
+    hp = p.hp
+    wss = [torch.empty(B.fae_bwd_workspace_bytes(hp.hot_tables, h.n_samples, h.n_lookups) + 256, dtype=torch.uint8, device=dev)
+           for h in hbs]
+    for h, ws in zip(hbs, wss):
+        B.fae_embbag_bwd_presort(hp.ctx, hp.hot_tables, h.batch(), ws)
+    for i in (2, 0, 5, 1, 4, 3):
+        h = hbs[i]
+        gout = S.upstream_grads(w, 60 + i, h.n_samples)
+        B.fae_embbag_bwd_sgd(hp.ctx, hp.hot_tables, hp.hotW, h.batch(), gout.to(dev), w.n_tables * w.dim, w.lr, wss[i])
+        hp.sync()
+        slots = [x.cpu().numpy() for x in h.slots]
+        offs = [None if o is None else o.cpu().numpy() for o in h.offsets]
+        uniq, _, mag = O.embbag_bwd_sgd(p.hotW, h.n_samples, slots, offs, gout.numpy(), w.lr, want_mag=True)
+        for z in range(w.n_tables):
+            if uniq[z].size:
+                got = hp.hotW[z][:p.n_hot[z]].cpu().numpy()
+                inh = p.wtol[z][uniq[z]].astype(np.float64)
+                T.assert_close_sum(got[uniq[z]], p.hotW[z][uniq[z]], mag[z], f"batch {i}, table {z}", inh)
+                p.wtol[z][uniq[z]] = (inh + T.RTOL * mag[z]).astype(np.float32) * np.float32(1.001)
+
+
 @pytest.mark.parametrize("reduce_variant", [1, 2])
 @pytest.mark.parametrize("wg_waves", [2, 4])
 def test_reduce_workgroup_sizes(dev, reduce_variant, wg_waves):
