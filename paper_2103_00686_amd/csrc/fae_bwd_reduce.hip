@@ -214,7 +214,8 @@ template <typename V, int LPR> __global__ __launch_bounds__(256) void bwd_reduce
     constexpr int VW = sizeof(V) / sizeof(float);
     constexpr int STEPS = FAE_WAVE / G;            // steps per tile of 64 lookups
     constexpr int UN = STEPS < 4 ? STEPS : 4;      // steps whose loads are issued together
-    const int sid = blockIdx.x * a.wg_waves + threadIdx.x / FAE_WAVE;
+    // the same for every lane of a wave: said so, the span's bookkeeping runs on the scalar unit
+    const int sid = blockIdx.x * a.wg_waves + __builtin_amdgcn_readfirstlane(threadIdx.x / FAE_WAVE);
     if (sid >= a.n_spans)
         return;
     const SpanInfo sp = bwd_span_info(a, sid);

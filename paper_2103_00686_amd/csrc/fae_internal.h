@@ -159,12 +159,35 @@ __device__ __forceinline__ void fae_flag(uint32_t *status, uint32_t bit)
     atomicOr(status + FAE_BLK_STATUS, bit);
 }
 
-// table that owns flat block index b, given exclusive prefix blk_start[0..nt]
+// table that owns flat block index b, given exclusive prefix blk_start[0..nt] (an array of
+// FAE_MAX_TABLES + 1 entries in the kernel's arguments).  The prefix is non-decreasing, so the
+// owner is the number of tables that start at or before b.  Counted in two rounds of seven
+// independent loads each (every eighth entry, then the entries of the group of eight found; one
+// round for up to eight tables):
+// a search that walks up to the owner is a chain of dependent loads as long as the table's
+// number, which the workgroups of the last tables pay in full before their first useful load.
 __device__ __forceinline__ int fae_find_table(const int32_t *blk_start, int nt, int b)
 {
-    int z = 0;
-    while (z + 1 < nt && b >= blk_start[z + 1])
-        ++z;
+    static_assert(FAE_MAX_TABLES == 64, "two levels of eight");
+    if (nt <= 1)
+        return 0;
+    int v[8]; // every load of a round is issued whatever the others return (the array has an entry for every index)
+    int base = 0;
+    if (nt > 8) {
+#pragma unroll
+        for (int i = 1; i < 8; ++i)
+            v[i] = blk_start[8 * i];
+#pragma unroll
+        for (int i = 1; i < 8; ++i)
+            base += ((8 * i < nt) & (b >= v[i])) ? 8 : 0;
+    }
+#pragma unroll
+    for (int i = 1; i < 8; ++i)
+        v[i] = blk_start[base + i];
+    int z = base;
+#pragma unroll
+    for (int i = 1; i < 8; ++i)
+        z += ((base + i < nt) & (b >= v[i])) ? 1 : 0;
     return z;
 }
 
