@@ -88,10 +88,10 @@ struct SpanInfo {
     bool head_open, tail_open;
 };
 
-__device__ __forceinline__ SpanInfo bwd_span_info(const BwdArgs &a, int sid)
+__device__ __forceinline__ SpanInfo bwd_span_info(const BwdArgs &a, int sid, int z)
 {
     SpanInfo s;
-    s.z = fae_find_table(a.blk_start, a.n_tables, sid);
+    s.z = z;
     s.local = sid - a.blk_start[s.z];
     s.seg0 = a.seg_start[s.z];
     s.seg1 = a.seg_start[s.z + 1];
@@ -216,9 +216,12 @@ template <typename V, int LPR> __global__ __launch_bounds__(256) void bwd_reduce
     constexpr int UN = STEPS < 4 ? STEPS : 4;      // steps whose loads are issued together
     // the same for every lane of a wave: said so, the span's bookkeeping runs on the scalar unit
     const int sid = blockIdx.x * a.wg_waves + __builtin_amdgcn_readfirstlane(threadIdx.x / FAE_WAVE);
+    // the table is looked up before the range check: kernel arguments only, so these loads leave
+    // together with the first ones instead of after them
+    const int z_of_span = fae_find_table(a.blk_start, a.n_tables, sid);
     if (sid >= a.n_spans)
         return;
-    const SpanInfo sp = bwd_span_info(a, sid);
+    const SpanInfo sp = bwd_span_info(a, sid, z_of_span);
     const int lane = fae_lane(), g = lane / LPR, l = lane % LPR;
     const int ncols = a.dim / VW;
     const int n_hot = a.n_hot[sp.z];
@@ -363,9 +366,12 @@ template <int LPR, int NB> __global__ __launch_bounds__(256) void bwd_reduce_wal
     __shared__ __align__(16) int lv[256 / FAE_WAVE][BWD_SPAN_MAX];
     const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x / FAE_WAVE);
     const int sid = blockIdx.x * a.wg_waves + wv;
+    // the table is looked up before the range check: kernel arguments only, so these loads leave
+    // together with the first ones instead of after them
+    const int z_of_span = fae_find_table(a.blk_start, a.n_tables, sid);
     if (sid >= a.n_spans)
         return;
-    const SpanInfo sp = bwd_span_info(a, sid);
+    const SpanInfo sp = bwd_span_info(a, sid, z_of_span);
     const int lane = fae_lane(), g = lane / LPR, l = lane % LPR;
     const int ncols = a.dim / 4;
     const int n_hot = a.n_hot[sp.z];
@@ -532,7 +538,7 @@ template <typename V, int LPR> __global__ __launch_bounds__(256) void bwd_fixup_
     const int lane = fae_lane(), g = lane / LPR, l = lane % LPR;
     // Two dependent rounds of memory traffic only: (1) the span's border keys together with the
     // first keys of the next 64 spans, (2) the partial sums together with the weight row.
-    const SpanInfo sp = bwd_span_info(a, sid);
+    const SpanInfo sp = bwd_span_info(a, sid, fae_find_table(a.blk_start, a.n_tables, sid));
     const int spans_z = a.blk_start[sp.z + 1] - a.blk_start[sp.z];
     const int j0 = sp.local + 1 + lane;
     const int follow_key = j0 < spans_z ? a.keys_in[sp.seg0 + j0 * a.span] : KEY_NONE;
