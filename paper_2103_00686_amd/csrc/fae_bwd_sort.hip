@@ -14,7 +14,8 @@
 
 // Four consecutive lookups of one thread: (slot, sample) pairs, 16-byte loads and stores when
 // aligned, plus the digit counts of every radix pass into the workgroup's LDS histograms.
-__device__ __forceinline__ void bwd_keys_thread(const BwdArgs &a, int z, int j0, int n, const int32_t *off, int s_first,
+// vs: the samples of the four lookups (tables with offsets; else a lookup is its own sample).
+__device__ __forceinline__ void bwd_keys_thread(const BwdArgs &a, int z, int j0, int n, const int32_t *off, const int *vs,
                                                 int (*s_hist)[RADIX])
 {
     const int32_t *slots = a.slots[z] + j0;
@@ -32,31 +33,20 @@ __device__ __forceinline__ void bwd_keys_thread(const BwdArgs &a, int z, int j0,
             k[q] = j0 + q < n ? slots[q] : 0;
     }
     bool bad = false;
-    int s = off ? s_first : 0;
 #pragma unroll
     for (int q = 0; q < KEYS_PER_THREAD; ++q) {
         const int j = j0 + q;
+        v[q] = j;
         if (j >= n)
-            break;
+            continue;
         if ((unsigned)k[q] >= (unsigned)a.n_hot[z]) {
             bad = true;
             k[q] = a.n_hot[z]; // sorts behind every valid slot of the table; never dereferenced
         }
         if (off) {
-            // bounded walk; a long stretch of empty bags falls back to a search
-            int steps = 0;
-            while (s + 1 < a.n_samples && off[s + 1] <= j) {
-                ++s;
-                if (++steps == 64) {
-                    s = fae_sample_of(off, a.n_samples, j);
-                    break;
-                }
-            }
-            if (off[s] > j || off[s + 1] <= j)
+            v[q] = vs[q]; // inside [0, n_samples) whatever the offsets hold
+            if (off[v[q]] > j || off[v[q] + 1] <= j)
                 bad = true; // malformed CSR
-            v[q] = s;
-        } else {
-            v[q] = j;
         }
     }
     if (bad)
@@ -81,27 +71,100 @@ __device__ __forceinline__ void bwd_keys_thread(const BwdArgs &a, int z, int j0,
     }
 }
 
+// how many of the workgroup's threads hold `flag` (every thread calls it; red: 256 / 64 + 1 ints)
+__device__ __forceinline__ int keys_block_count(bool flag, int *red)
+{
+    const int c = __popcll(__ballot(flag));
+    __syncthreads(); // red may still be read from a previous call
+    if (fae_lane() == 0)
+        red[threadIdx.x / FAE_WAVE] = c;
+    __syncthreads();
+    return red[0] + red[1] + red[2] + red[3];
+}
 
 // Each thread handles four consecutive lookups (16-byte loads and stores when aligned).
+// Tables with offsets: which sample a lookup belongs to is found by the workgroup together.
+//   1. the sample of the workgroup's first lookup: an upper-bound search over the offsets in
+//      which every round probes 256 evenly spaced entries at once (three dependent loads for
+//      65 536 samples, where a search by one thread makes seventeen);
+//   2. every later bag that starts among the workgroup's 1024 lookups marks its first lookup
+//      with its sample number (the largest one wins where empty bags share a start);
+//   3. a running maximum over the marks gives every lookup its sample.
 __global__ __launch_bounds__(256) void bwd_keys_kernel(BwdArgs a)
 {
+    static_assert(KEYS_PER_BLOCK == 256 * KEYS_PER_THREAD, "one workgroup of 256 threads per block of lookups");
     const int z = fae_find_table(a.blk_start, a.n_tables, blockIdx.x);
-    const int j0 = (blockIdx.x - a.blk_start[z]) * KEYS_PER_BLOCK + threadIdx.x * KEYS_PER_THREAD;
+    const int jb = (blockIdx.x - a.blk_start[z]) * KEYS_PER_BLOCK; // the workgroup's first lookup (inside the table)
+    const int j0 = jb + threadIdx.x * KEYS_PER_THREAD;
     const int n = a.seg_start[z + 1] - a.seg_start[z];
     const int32_t *off = a.offsets[z];
-    // sample of a lookup: one binary search per workgroup (its first lookup), then every thread
-    // walks forward from there (a workgroup's lookups span few bags)
-    __shared__ int s_first;
     __shared__ int s_hist[SWEEP_MAX_PASSES][RADIX];
-    if (off && threadIdx.x == 0) {
-        const int jb = (blockIdx.x - a.blk_start[z]) * KEYS_PER_BLOCK;
-        s_first = fae_sample_of(off, a.n_samples, jb < n ? jb : n - 1);
-    }
+    __shared__ int s_mark[KEYS_PER_BLOCK];
+    __shared__ int s_red[256 / FAE_WAVE + 1];
     for (int p = 0; p < a.n_passes; ++p)
         s_hist[p][threadIdx.x] = 0;
+    int vs[KEYS_PER_THREAD] = {0, 0, 0, 0};
+    if (off) {
+        const int jend = jb + KEYS_PER_BLOCK < n ? jb + KEYS_PER_BLOCK : n;
+#pragma unroll
+        for (int q = 0; q < KEYS_PER_THREAD; ++q)
+            s_mark[threadIdx.x * KEYS_PER_THREAD + q] = -1;
+        // 1. entries of offsets[0 .. n_samples] that are <= jb: all before lo are, none from hi on is
+        int lo = 0, hi = a.n_samples + 1;
+        while (hi - lo > 256) {
+            const int step = (hi - lo + 255) / 256;
+            const int64_t idx = (int64_t)lo + (int64_t)(threadIdx.x + 1) * step - 1; // last entry of piece threadIdx.x
+            const bool le = idx < hi && off[idx] <= jb;
+            const int c = keys_block_count(le, s_red); // pieces that lie wholly at or below jb
+            lo += c * step;
+            hi = lo + step < hi ? lo + step : hi;
+        }
+        const bool le = lo + (int)threadIdx.x < hi && off[lo + threadIdx.x] <= jb;
+        int s_first = lo + keys_block_count(le, s_red) - 1;
+        s_first = s_first < 0 ? 0 : (s_first >= a.n_samples ? a.n_samples - 1 : s_first);
+        // 2. (also orders the clearing of s_mark above before the marks: keys_block_count has barriers)
+        for (int64_t s = (int64_t)s_first + 1 + threadIdx.x; s < a.n_samples; s += 256) {
+            const int o = off[s];
+            if (o >= jend)
+                break;
+            if (o >= jb)
+                atomicMax(&s_mark[o - jb], (int)s);
+        }
+        __syncthreads();
+        // 3. inclusive running maximum, four positions per thread
+        int m[KEYS_PER_THREAD];
+        int own = -1;
+#pragma unroll
+        for (int q = 0; q < KEYS_PER_THREAD; ++q) {
+            m[q] = s_mark[threadIdx.x * KEYS_PER_THREAD + q];
+            own = own > m[q] ? own : m[q];
+        }
+        int run = own; // maximum over this and the earlier threads of the wave
+#pragma unroll
+        for (int d = 1; d < FAE_WAVE; d <<= 1) {
+            const int o = __shfl_up(run, d, FAE_WAVE);
+            if (fae_lane() >= d)
+                run = run > o ? run : o;
+        }
+        __syncthreads(); // s_red was read by keys_block_count
+        if (fae_lane() == FAE_WAVE - 1)
+            s_red[threadIdx.x / FAE_WAVE] = run;
+        __syncthreads();
+        int before = s_first; // everything in front of this thread's positions
+        for (int w = 0; w < (int)(threadIdx.x / FAE_WAVE); ++w)
+            before = before > s_red[w] ? before : s_red[w];
+        const int prev = __shfl_up(run, 1, FAE_WAVE);
+        if (fae_lane() > 0)
+            before = before > prev ? before : prev;
+#pragma unroll
+        for (int q = 0; q < KEYS_PER_THREAD; ++q) {
+            before = before > m[q] ? before : m[q];
+            vs[q] = before;
+        }
+    }
     __syncthreads();
     if (j0 < n)
-        bwd_keys_thread(a, z, j0, n, off, s_first, s_hist);
+        bwd_keys_thread(a, z, j0, n, off, vs, s_hist);
     if (a.n_passes > 0) {
         __syncthreads();
         for (int p = 0; p < a.n_passes; ++p) {
