@@ -43,10 +43,11 @@ def main():
     ap.add_argument("--set", action="append", default=[], help="library option name=value (ablation)")
     ap.add_argument("--graph", action="store_true",
                     help="capture each step into a HIP graph and time the replays (same kernels, fewer launches)")
-    ap.add_argument("--presort", choices=["fused", "side", "none", "ahead"], default="fused",
-                    help="where the backward's sort runs: in the forward's launch (default, where the shape "
-                         "allows), on the side stream, inside fae_embbag_bwd_sgd, or one step ahead on the side "
-                         "stream (the next batch's sort beside this batch's forward and backward)")
+    ap.add_argument("--presort", choices=["auto", "fused", "side", "none", "ahead"], default="auto",
+                    help="where the backward's sort runs: in the forward's launch (fused; needs one-hot tables "
+                         "and at most 16384 samples), on the side stream, inside fae_embbag_bwd_sgd, or one step "
+                         "ahead on the side stream (the next batch's sort beside this batch's forward and "
+                         "backward).  auto: fused where the shape allows, else ahead")
     args = ap.parse_args()
     if args.graph and args.presort == "ahead":
         print("bench.py: --graph captures one stream; --presort ahead uses two", file=sys.stderr)
@@ -173,10 +174,14 @@ def run_workload(args, cfg_id, n_steps, n_warmup, with_cpu):
     outs = [torch.empty((hb.n_samples, nt, D), dtype=torch.float32, device=dev) for hb in batches]
     ws_need = max(B.fae_bwd_workspace_bytes(hp.hot_tables, hb.n_samples, hb.n_lookups) for hb in batches)
     hp._workspace("bwd", ws_need)
-    if args.presort == "ahead":
+    presort = args.presort
+    if presort == "auto":
+        fusable = all(o is None for hb in batches for o in hb.offsets) and max(hb.n_samples for hb in batches) <= 16384
+        presort = "fused" if fusable or args.graph else "ahead"
+    if presort == "ahead":
         steps_fn = hp.prepare_pipeline(batches, gouts, outs, w.lr)
     else:
-        steps_fn = [hp.prepare_step(hb, g, o, w.lr, presort=args.presort) for hb, g, o in zip(batches, gouts, outs)]
+        steps_fn = [hp.prepare_step(hb, g, o, w.lr, presort=presort) for hb, g, o in zip(batches, gouts, outs)]
 
     # accounting per batch: lookups, bags, distinct rows
     acct = []
@@ -332,7 +337,7 @@ def run_workload(args, cfg_id, n_steps, n_warmup, with_cpu):
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": w.name, "config_index": cfg_id, "tables": nt, "dim": D, "batch": w.batch,
                    "zipf_s": w.zipf_s, "hot_rows": int(sum(hp.n_hot)), "hot_bytes": int(sum(hp.n_hot)) * D * 4,
-                   "cutoff_c": c, "lookups_per_step": NL, "distinct_rows_per_step": U, "hot_batches": nb, "launch": "hip graph replay" if args.graph else "eager",
+                   "cutoff_c": c, "lookups_per_step": NL, "distinct_rows_per_step": U, "hot_batches": nb, "launch": "hip graph replay" if args.graph else "eager", "presort": presort,
                    "profile_samples": w.profile_samples},
         "roofline": roofline, "cpu_baseline": cpu, "stages": {k: float(f"{v:.4g}") for k, v in stages.items()},
     }
