@@ -649,13 +649,15 @@ extern "C" int32_t fae_embbag_bwd_presort(fae_ctx *ctx, const fae_tables *hot_ta
         return FAE_OK;
     // fork: the side stream starts after everything already queued on the main stream
     // (earlier users of this workspace, producers of the slots)
-    FAE_HIP(ctx, hipEventRecord(ctx->ev_fork, ctx->stream));
-    FAE_HIP(ctx, hipStreamWaitEvent(ctx->aux_stream, ctx->ev_fork, 0));
+    const int side = ctx->aux_next;
+    ctx->aux_next = (side + 1) % fae_ctx::N_AUX;
+    FAE_HIP(ctx, hipEventRecord(ctx->ev_fork[side], ctx->stream));
+    FAE_HIP(ctx, hipStreamWaitEvent(ctx->aux_stream[side], ctx->ev_fork[side], 0));
     int cur = 0;
-    rc = bwd_sort_stage(ctx, ctx->aux_stream, hot_tables, hot_batch, su, &cur);
+    rc = bwd_sort_stage(ctx, ctx->aux_stream[side], hot_tables, hot_batch, su, &cur);
     if (rc != FAE_OK)
         return rc;
-    FAE_HIP(ctx, hipEventRecord(ps->ev_join, ctx->aux_stream));
+    FAE_HIP(ctx, hipEventRecord(ps->ev_join, ctx->aux_stream[side]));
     ps->valid = true;
     ps->side = true;
     ps->ws = ws;

@@ -24,6 +24,15 @@ __global__ void fae_clear_words_kernel(uint32_t *p, int n)
         p[i] = 0u;
 }
 
+static bool fae_make_side_streams(fae_ctx *ctx)
+{
+    for (int i = 0; i < fae_ctx::N_AUX; ++i)
+        if (hipStreamCreateWithFlags(&ctx->aux_stream[i], hipStreamNonBlocking) != hipSuccess ||
+            hipEventCreateWithFlags(&ctx->ev_fork[i], hipEventDisableTiming) != hipSuccess)
+            return false;
+    return true;
+}
+
 static bool fae_make_join_events(fae_ctx *ctx)
 {
     for (auto &e : ctx->presort)
@@ -66,9 +75,7 @@ extern "C" int32_t fae_create(fae_ctx **out, int32_t device, void *hip_stream)
         return FAE_EHIP;
     }
     memset(ctx->h_block, 0, FAE_BLK_WORDS * sizeof(uint32_t));
-    if (hipStreamCreateWithFlags(&ctx->aux_stream, hipStreamNonBlocking) != hipSuccess ||
-        hipEventCreateWithFlags(&ctx->ev_fork, hipEventDisableTiming) != hipSuccess ||
-        !fae_make_join_events(ctx)) {
+    if (!fae_make_side_streams(ctx) || !fae_make_join_events(ctx)) {
         (void)hipFree(ctx->d_block);
         (void)hipHostFree(ctx->h_block);
         delete ctx;
@@ -92,12 +99,14 @@ extern "C" void fae_destroy(fae_ctx *ctx)
         return;
     (void)hipSetDevice(ctx->device);
     (void)hipStreamSynchronize(ctx->stream);
-    if (ctx->aux_stream) {
-        (void)hipStreamSynchronize(ctx->aux_stream);
-        (void)hipStreamDestroy(ctx->aux_stream);
+    for (int i = 0; i < fae_ctx::N_AUX; ++i) {
+        if (ctx->aux_stream[i]) {
+            (void)hipStreamSynchronize(ctx->aux_stream[i]);
+            (void)hipStreamDestroy(ctx->aux_stream[i]);
+        }
+        if (ctx->ev_fork[i])
+            (void)hipEventDestroy(ctx->ev_fork[i]);
     }
-    if (ctx->ev_fork)
-        (void)hipEventDestroy(ctx->ev_fork);
     for (auto &e : ctx->presort)
         if (e.ev_join)
             (void)hipEventDestroy(e.ev_join);
@@ -154,7 +163,8 @@ fae_ktimer::~fae_ktimer()
 static int32_t timing_collect(fae_ctx *ctx)
 {
     FAE_HIP(ctx, hipStreamSynchronize(ctx->stream));
-    FAE_HIP(ctx, hipStreamSynchronize(ctx->aux_stream));
+    for (int i = 0; i < fae_ctx::N_AUX; ++i)
+        FAE_HIP(ctx, hipStreamSynchronize(ctx->aux_stream[i]));
     for (const fae_timed_launch &t : ctx->timed) {
         float ms = 0.f;
         if (hipEventElapsedTime(&ms, t.e0, t.e1) == hipSuccess) {
@@ -250,8 +260,9 @@ int32_t fae_readback(fae_ctx *ctx, int first, int n)
 
 int32_t fae_sync_status(fae_ctx *ctx)
 {
-    if (ctx->aux_stream)
-        FAE_HIP(ctx, hipStreamSynchronize(ctx->aux_stream));
+    for (int i = 0; i < fae_ctx::N_AUX; ++i)
+        if (ctx->aux_stream[i])
+            FAE_HIP(ctx, hipStreamSynchronize(ctx->aux_stream[i]));
     int32_t rc = fae_readback(ctx, FAE_BLK_STATUS, 1);
     if (rc != FAE_OK)
         return rc;

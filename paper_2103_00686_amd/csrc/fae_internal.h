@@ -44,8 +44,11 @@ struct fae_ctx {
     int64_t opt_unroll = 0;     // gradient rows in flight per lane group in the second form (0 = auto, 4, 8)
     char err[512] = {0};
     // side stream for work that may overlap the main stream (backward presort)
-    hipStream_t aux_stream = nullptr;
-    hipEvent_t ev_fork = nullptr;
+    // two of them, taken in turn: the sorts of consecutive batches may overlap each other
+    static constexpr int N_AUX = 2;
+    hipStream_t aux_stream[N_AUX] = {nullptr, nullptr};
+    hipEvent_t ev_fork[N_AUX] = {nullptr, nullptr};
+    int aux_next = 0;
     // Sorted (slot, sample) pairs waiting for their backward call, one entry per workspace: a
     // caller may sort the next batch (into a second workspace) while this one is still in use.
     static constexpr int N_PRESORT = 4;
