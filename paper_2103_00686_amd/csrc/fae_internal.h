@@ -220,6 +220,8 @@ __device__ __forceinline__ int fae_wave_incl_scan(int v)
 
 // exclusive scan across a block of BLOCK threads (BLOCK multiple of 64, <= 1024).
 // lds must hold BLOCK/64 + 1 ints.  Returns the exclusive prefix; *total = block sum.
+// Every thread adds up the wave totals itself (at most sixteen LDS reads of the same addresses,
+// issued together): no thread does it for the others while they wait at a third barrier.
 template <int BLOCK> __device__ __forceinline__ int fae_block_excl_scan(int v, int *lds, int *total)
 {
     constexpr int NW = BLOCK / FAE_WAVE;
@@ -229,18 +231,15 @@ template <int BLOCK> __device__ __forceinline__ int fae_block_excl_scan(int v, i
     if (lane == FAE_WAVE - 1)
         lds[w] = inc;
     __syncthreads();
-    if (threadIdx.x == 0) {
-        int run = 0;
-        for (int i = 0; i < NW; ++i) {
-            int t = lds[i];
-            lds[i] = run;
-            run += t;
-        }
-        lds[NW] = run;
+    int before = 0, all = 0;
+#pragma unroll
+    for (int i = 0; i < NW; ++i) {
+        const int t = lds[i];
+        all += t;
+        before += i < w ? t : 0;
     }
-    __syncthreads();
-    *total = lds[NW];
-    return lds[w] + inc - v;
+    *total = all;
+    return before + inc - v;
 }
 
 // first position in sorted a[lo,hi) whose value is > key (upper bound)
