@@ -183,6 +183,8 @@ __device__ __forceinline__ int lds_radix_passes(const int *keys, int sub, int n_
             uint64_t peers = __ballot(valid);
 #pragma unroll
             for (int b = 0; b < RADIX_BITS; ++b) {
+                if (b >= digit_bits)
+                    break; // the digits of this sort are narrower than a byte
                 const bool bit = (d >> b) & 1;
                 const uint64_t m = __ballot(bit);
                 peers &= bit ? m : ~m;
