@@ -47,7 +47,7 @@ def main():
                     help="where the backward's sort runs: in the forward's launch (fused; needs one-hot tables "
                          "and at most 16384 samples), on the side stream, inside fae_embbag_bwd_sgd, or one step "
                          "ahead on the side stream (the next batch's sort beside this batch's forward and "
-                         "backward).  auto: fused where the shape allows, else ahead")
+                         "backward).  auto: fused where the shape allows, else ahead for steps of up to 4 M lookups")
     args = ap.parse_args()
     if args.graph and args.presort == "ahead":
         print("bench.py: --graph captures one stream; --presort ahead uses two", file=sys.stderr)
@@ -177,7 +177,9 @@ def run_workload(args, cfg_id, n_steps, n_warmup, with_cpu):
     presort = args.presort
     if presort == "auto":
         fusable = all(o is None for hb in batches for o in hb.offsets) and max(hb.n_samples for hb in batches) <= 16384
-        presort = "fused" if fusable or args.graph else "ahead"
+        # sorting ahead hides a string of short launches; long bandwidth-bound sort passes gain nothing from it
+        short_sort = max(sum(hb.n_lookups) for hb in batches) <= (1 << 22)
+        presort = "ahead" if (not fusable and short_sort and not args.graph) else "fused"
     if presort == "ahead":
         steps_fn = hp.prepare_pipeline(batches, gouts, outs, w.lr)
     else:
