@@ -276,6 +276,36 @@ def test_backward_long_runs_and_many_tiles(dev, S_, sort_variant, reduce_variant
     assert abs(total - float(np.abs(got).astype(np.float64).sum())) < 1e-6 * max(total, 1.0)
 
 
+@pytest.mark.parametrize("nt,S_,fused", [(64, 300, True), (64, 300, False), (37, 5000, True), (3, 16384, True), (3, 16385, True),
+                                         (2, 16385, False)])
+def test_table_count_and_sort_tier_limits(dev, nt, S_, fused):
+    """The largest number of tables (the table of a workgroup is looked up in two rounds over the
+    whole prefix of 65 entries), a count in between, and batches on either side of what the LDS
+    sort and the fused forward + sort launch take (16 384 lookups per table); tables of very
+    different sizes, one of them a single row."""
+    rng = np.random.default_rng(nt * 100003 + S_)
+    dim, lr = 8, 0.05
+    n_hot = [int(x) for x in rng.integers(1, 3000, nt)]
+    n_hot[0], n_hot[-1] = 1, 70_000
+    hp = HotPath(n_hot, dim, 0)
+    hp.n_hot = n_hot
+    Wref = [(rng.random((n, dim), dtype=np.float32) - 0.5) for n in n_hot]
+    hp.hotW = [torch.from_numpy(x).to(dev) for x in Wref]
+    slots = [rng.integers(0, n, S_).astype(np.int32) for n in n_hot]
+    hb = HotBatch(S_, [torch.from_numpy(x).to(dev) for x in slots], [None] * nt, [S_] * nt)
+    out = (hp.forward_presort(hb) if fused else hp.forward(hb)).cpu().numpy()
+    ref, mag = O.embbag_fwd(Wref, S_, slots, [None] * nt, want_mag=True)
+    T.assert_close_sum(out, ref, mag, "forward")
+    assert out.tobytes() == ref.tobytes()   # one-hot: a gather, no arithmetic
+    gout = torch.from_numpy(rng.standard_normal((S_, nt, dim)).astype(np.float32))
+    dbg = hp.backward_sgd(hb, gout.to(dev), lr, debug=True)
+    hp.sync()
+    uniq, runlen, mg = O.embbag_bwd_sgd(Wref, S_, slots, [None] * nt, gout.numpy(), lr, want_mag=True)
+    for z in range(nt):
+        assert np.array_equal(dbg[0][z].cpu().numpy(), uniq[z]) and np.array_equal(dbg[1][z].cpu().numpy(), runlen[z])
+        T.assert_close_sum(hp.hotW[z].cpu().numpy()[uniq[z]], Wref[z][uniq[z]], mg[z], f"table {z}")
+
+
 def test_integer_valued_case_is_bit_exact(dev):
     """Integer weights/gradients and lr a power of two: every summation order is exact, so
     forward and update must match the oracle bit for bit."""
