@@ -83,6 +83,7 @@ struct LsortArgs {
     int32_t part_shift[FAE_MAX_TABLES];    // part of a key = key >> part_shift
     int32_t n_tables;
     int32_t n_samples;
+    int32_t unordered; // counting sort: the order inside a slot's run is left to the hardware
     int32_t *keys_out, *vals_out;
     uint32_t *status;
     int32_t *flags; // span flags of the reduce kernel, zeroed here

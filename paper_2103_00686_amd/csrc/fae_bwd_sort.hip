@@ -418,7 +418,7 @@ __global__ __launch_bounds__(LSORT_THREADS) void lds_sort_kernel(LsortArgs a)
     const int z = fae_find_table(a.blk_start, a.n_tables, blockIdx.x);
     lds_sort_block(a.slots[z], a.offsets[z], a.seg_start[z + 1] - a.seg_start[z], a.n_hot[z],
                    blockIdx.x - a.blk_start[z], a.part_shift[z], a.n_samples, a.keys_out + a.seg_start[z],
-                   a.vals_out + a.seg_start[z], a.status);
+                   a.vals_out + a.seg_start[z], a.status, a.unordered != 0);
 }
 
 // ---------------------------------------------------------------------------------
@@ -622,6 +622,7 @@ int32_t bwd_sort_stage(fae_ctx *ctx, hipStream_t st, const fae_tables *hot_table
         la.keys_out = w.keys[cur];
         la.vals_out = w.vals[cur];
         la.status = ctx->d_block;
+        la.unordered = ctx->opt_sort_order == 1;
         la.flags = a.flags;
         la.n_flags = a.n_flags;
         la.flag_slice = bwd_flag_slice(a.n_flags, nb);
@@ -684,6 +685,7 @@ struct FusedArgs {
     int32_t part_shift[FAE_MAX_TABLES];
     int32_t n_tables, dim, n_samples;
     int32_t n_sort_blocks, fwd_blocks_per_table;
+    int32_t unordered;
     int64_t out_stride;
     float *out;
     int32_t *keys_out, *vals_out;
@@ -700,7 +702,7 @@ template <typename V, int LPR> __global__ __launch_bounds__(LSORT_THREADS) void 
         const int z = fae_find_table(a.sort_blk_start, a.n_tables, blockIdx.x);
         lds_sort_block(a.slots[z], nullptr, a.seg_start[z + 1] - a.seg_start[z], a.n_hot[z],
                        blockIdx.x - a.sort_blk_start[z], a.part_shift[z], a.n_samples, a.keys_out + a.seg_start[z],
-                       a.vals_out + a.seg_start[z], a.status);
+                       a.vals_out + a.seg_start[z], a.status, a.unordered != 0);
     } else {
         const int b = blockIdx.x - a.n_sort_blocks;
         const int z = b / a.fwd_blocks_per_table, bl = b % a.fwd_blocks_per_table;
@@ -760,6 +762,7 @@ extern "C" int32_t fae_embbag_fwd_presort(fae_ctx *ctx, const fae_tables *hot_ta
     f.keys_out = su.w.keys[0];
     f.vals_out = su.w.vals[0];
     f.status = ctx->d_block;
+    f.unordered = ctx->opt_sort_order == 1;
     f.stream_out = ctx->opt_fwd_stream != 0;
     f.flags = su.a.flags;
     f.n_flags = su.a.n_flags;

@@ -232,6 +232,8 @@ extern "C" int32_t fae_set_option(fae_ctx *ctx, const char *name, int64_t value)
         ctx->opt_fwd = value;
     else if (!strcmp(name, "sort_variant") && value >= 0 && value <= 4)
         ctx->opt_sort = value;
+    else if (!strcmp(name, "sort_order") && value >= 0 && value <= 1)
+        ctx->opt_sort_order = value;
     else if (!strcmp(name, "fwd_stream_out") && value >= 0 && value <= 1)
         ctx->opt_fwd_stream = value;
     else if (!strcmp(name, "reduce_span") && (value == 0 || value == 64 || value == 128 || value == 256))

@@ -207,7 +207,7 @@ __device__ __forceinline__ int lds_radix_passes(const int *keys, int sub, int n_
 
 __device__ __forceinline__ void lds_sort_block(const int32_t *slots, const int32_t *off, int n, int n_hot, int part,
                                                int pshift, int n_samples, int32_t *keys_out, int32_t *vals_out,
-                                               uint32_t *status)
+                                               uint32_t *status, bool unordered)
 {
     __shared__ __align__(16) int keyA[LSORT_MAX];
     __shared__ unsigned short perm[2][LSORT_MAX];
@@ -248,6 +248,62 @@ __device__ __forceinline__ void lds_sort_block(const int32_t *slots, const int32
         } else {
             kk[i] = -1; // in no part
         }
+    }
+    if (unordered && pshift < 31 && (1 << pshift) <= LSORT_MAX) {
+        // Counting sort: one counter per slot of the part's range (they take the place of the keys in
+        // LDS; the keys stay in registers), a scan, and every lookup takes the next free place of its
+        // slot.  One sweep each way instead of two ranked radix passes; which lookup of a slot gets
+        // which place is left to the order in which the LDS serves the atomics.
+        int *cnt = keyA;
+        const int range = 1 << pshift, lo = part << pshift;
+        for (int i = threadIdx.x; i < range; i += LSORT_THREADS)
+            cnt[i] = 0;
+        if (bad && part == 0)
+            fae_flag(status, FAE_STATUS_ERANGE);
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < PER; ++i)
+            if (kk[i] >= 0 && (kk[i] >> pshift) == part)
+                atomicAdd(&cnt[kk[i] - lo], 1);
+        int n_below;
+        (void)fae_block_excl_scan<LSORT_THREADS>(below, scan_lds, &n_below); // its barriers also end the counting
+        const int per = (range + LSORT_THREADS - 1) / LSORT_THREADS; // counters per thread, <= PER
+        int c[PER], own = 0;
+#pragma unroll
+        for (int i = 0; i < PER; ++i) {
+            const int r = threadIdx.x * per + i;
+            c[i] = (i < per && r < range) ? cnt[r] : 0;
+            own += c[i];
+        }
+        int n_part;
+        int at = fae_block_excl_scan<LSORT_THREADS>(own, scan_lds, &n_part);
+#pragma unroll
+        for (int i = 0; i < PER; ++i) {
+            const int r = threadIdx.x * per + i;
+            if (i < per && r < range)
+                cnt[r] = at;
+            at += c[i];
+        }
+        __syncthreads();
+        bad = false;
+#pragma unroll
+        for (int i = 0; i < PER; ++i) {
+            if (kk[i] < 0 || (kk[i] >> pshift) != part)
+                continue;
+            const int e = e0 + i;
+            int sm = e;
+            if (off) {
+                sm = fae_sample_of(off, n_samples, e);
+                if (off[sm] > e || off[sm + 1] <= e)
+                    bad = true; // malformed CSR
+            }
+            const int place = n_below + atomicAdd(&cnt[kk[i] - lo], 1);
+            keys_out[place] = kk[i];
+            vals_out[place] = sm;
+        }
+        if (bad)
+            fae_flag(status, FAE_STATUS_ERANGE);
+        return;
     }
 #pragma unroll
     for (int i = 0; i < PER; i += 4)

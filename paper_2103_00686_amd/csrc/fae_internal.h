@@ -36,6 +36,7 @@ struct fae_ctx {
     int64_t opt_profile = 0; // 0 auto, 1 global atomics, 2 LDS-privatised
     int64_t opt_fwd = 0;     // 0 auto, 1 group-per-bag, 2 wave-per-bag
     int64_t opt_sort = 0;    // 0 auto, 1 global radix, 2 LDS per table
+    int64_t opt_sort_order = 0; // LDS sort: 0 stable (lookups of a slot in batch order), 1 counting sort (any order)
     int64_t opt_fwd_stream = 1; // non-temporal stores for the pooled output
     int64_t opt_span = 0;       // lookups per wave in the reduce kernel (0 = auto)
     int64_t opt_fixup = 0;      // runs that cross span borders: 0 auto (inside the reduce kernel), 1 separate kernel

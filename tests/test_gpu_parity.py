@@ -163,6 +163,24 @@ def test_more_sorted_workspaces_than_the_library_remembers(dev):
                 p.wtol[z][uniq[z]] = (inh + T.RTOL * mag[z]).astype(np.float32) * np.float32(1.001)
 
 
+@pytest.mark.parametrize("cfg_id", [1, 2, 3, 4])
+def test_counting_sort_in_lds(dev, cfg_id):
+    """sort_order=1: the LDS sort places lookups by counting (no ranked radix passes), so the
+    lookups of a slot come in any order.  Distinct slots and multiplicities stay exact, sums stay
+    within the bound; through the separate calls and through the fused forward + sort launch."""
+    w = S.workload(cfg_id, "test")
+    p = T.Pipeline(w, dev, profile_chunks=1)
+    B.fae_set_option(p.hp.ctx, "sort_order", 1)
+    p.check_profile()
+    p.check_cutoff()
+    p.check_build()
+    batches = T.hot_batches(p, 2)
+    p.check_backward(batches[0], stream=50)
+    p.check_forward(batches[-1], exact_gather=False, fused=True)
+    p.check_backward(batches[-1], stream=51)
+    p.check_backward(batches[0], stream=52, presort=batches[0])
+
+
 @pytest.mark.parametrize("reduce_variant", [1, 2])
 @pytest.mark.parametrize("wg_waves", [2, 4])
 def test_reduce_workgroup_sizes(dev, reduce_variant, wg_waves):
