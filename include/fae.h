@@ -104,7 +104,9 @@ int32_t fae_sync(fae_ctx *ctx);
  * 2=LDS-privatised), ("fwd_variant", 0=auto 1=group-per-bag 2=wave-per-bag),
  * ("sort_variant", 0=auto, 1=global radix with three kernels per pass, 2=LDS per table
  * where it fits, 3=global radix with one kernel per pass, 4=the same with tiles handed out
- * by a counter), ("reduce_variant", 0=auto
+ * by a counter), ("sort_order", 0=the lookups of a slot stay in batch order, 1=the LDS sort
+ * places lookups by counting: faster on small batches, but the order inside a slot's run, and
+ * with it the last bits of the updated weights, may differ from run to run), ("reduce_variant", 0=auto
  * 1=segmented scan across lane groups 2=a share of the span per lane group),
  * ("reduce_span", 0/64/128/256 sorted lookups per wave), ("reduce_unroll", 0/4/8 gradient
  * rows in flight per lane group, second form only), ("reduce_wg_waves", 0=auto (1)/1/2/4
