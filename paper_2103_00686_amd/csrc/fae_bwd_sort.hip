@@ -428,12 +428,18 @@ __global__ __launch_bounds__(LSORT_THREADS) void lds_sort_kernel(LsortArgs a)
 // below ~512 lookups.  part_shift[z]: part of a key = key >> shift; blk_start: prefix of
 // workgroups per table (tables not sorted in LDS get none).  Returns the number of workgroups.
 static int lsort_plan(const fae_ctx *ctx, const fae_tables *hot_tables, const fae_batch *hot_batch, const bool *in_lds,
-               int n_lds, int32_t *blk_start, int32_t *part_shift)
+               int n_lds, int32_t *blk_start, int32_t *part_shift, int64_t other_blocks)
 {
     const int nt = hot_tables->n_tables;
     int want = 1;
     while (want < 16 && n_lds * want * 2 <= ctx->n_cu)
         want <<= 1;
+    // In the launch that also copies rows (other_blocks workgroups of them, one workgroup per
+    // compute unit), every sorting workgroup keeps a unit from copying: when the copies alone are
+    // more than the chip holds at once, fewer and larger parts win although the largest part ends
+    // later (workload 3: 35.5 us with 4 parts per table, 38.9 us with 8, 43.5 us with 2).
+    while (want > 4 && (int64_t)n_lds * want + other_blocks > (int64_t)ctx->n_cu * 3 / 2)
+        want >>= 1;
     int nb = 0;
     for (int z = 0; z < nt; ++z) {
         blk_start[z] = nb;
@@ -615,7 +621,7 @@ int32_t bwd_sort_stage(fae_ctx *ctx, hipStream_t st, const fae_tables *hot_table
             la.n_hot[z] = a.n_hot[z];
             la.seg_start[z] = a.seg_start[z];
         }
-        const int nb = lsort_plan(ctx, hot_tables, hot_batch, in_lds, n_lds, la.blk_start, la.part_shift);
+        const int nb = lsort_plan(ctx, hot_tables, hot_batch, in_lds, n_lds, la.blk_start, la.part_shift, 0);
         la.seg_start[nt] = a.seg_start[nt];
         la.n_tables = nt;
         la.n_samples = a.n_samples;
@@ -752,7 +758,8 @@ extern "C" int32_t fae_embbag_fwd_presort(fae_ctx *ctx, const fae_tables *hot_ta
         in_lds[z] = true;
     }
     f.seg_start[nt] = su.a.seg_start[nt];
-    f.n_sort_blocks = lsort_plan(ctx, hot_tables, hot_batch, in_lds, nt, f.sort_blk_start, f.part_shift);
+    f.n_sort_blocks = lsort_plan(ctx, hot_tables, hot_batch, in_lds, nt, f.sort_blk_start, f.part_shift,
+                                (int64_t)nt * ((S + LSORT_THREADS - 1) / LSORT_THREADS));
     f.n_tables = nt;
     f.dim = dim;
     f.n_samples = (int32_t)S;
