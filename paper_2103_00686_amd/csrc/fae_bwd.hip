@@ -16,7 +16,8 @@
 //              sums are published in a small scratch array and the span in which the
 //              run ends adds them in span order and applies the update (inside the
 //              reduce kernel; as a kernel of its own for very wide rows or on request).
-// No float atomics: every row has exactly one writer and a fixed summation order.
+// No float atomics: every row has exactly one writer, and the summation order is fixed by the
+// stable sort (the optional counting sort, sort_order=1, leaves the order inside a run open).
 // Bandwidth bound: per lookup one gradient row is read, per distinct row one weight
 // row is read and written; the sort moves 16 B per lookup and pass.
 //

@@ -1,8 +1,8 @@
 // Backward, steps 3 + 4: segment reduce of the sorted lookups and the optimizer step on the hot
 // tables (Sec. 2.2, Sec. 6.2).  One wave owns a span of sorted lookups; runs inside the span get
 // their update at once, runs that cross span borders are finished by the span in which they end
-// (or by the fix-up kernel).  No float atomics: every row has one writer and a fixed summation
-// order.  Also here: the optional outputs for bit-exact checking (distinct slots, multiplicities).
+// (or by the fix-up kernel).  No float atomics: every row has one writer, and the sums are added
+// in the order the sort stage delivers the lookups.  Also here: the optional outputs for bit-exact checking (distinct slots, multiplicities).
 #include "fae_bwd.h"
 
 // ---------------------------------------------------------------------------------
