@@ -174,16 +174,7 @@ def run_workload(args, cfg_id, n_steps, n_warmup, with_cpu):
     outs = [torch.empty((hb.n_samples, nt, D), dtype=torch.float32, device=dev) for hb in batches]
     ws_need = max(B.fae_bwd_workspace_bytes(hp.hot_tables, hb.n_samples, hb.n_lookups) for hb in batches)
     hp._workspace("bwd", ws_need)
-    presort = args.presort
-    if presort == "auto":
-        fusable = all(o is None for hb in batches for o in hb.offsets) and max(hb.n_samples for hb in batches) <= 16384
-        # sorting ahead hides a string of short launches; long bandwidth-bound sort passes gain nothing from it
-        short_sort = max(sum(hb.n_lookups) for hb in batches) <= (1 << 22)
-        presort = "ahead" if (not fusable and short_sort and not args.graph) else "fused"
-    if presort == "ahead":
-        steps_fn = hp.prepare_pipeline(batches, gouts, outs, w.lr)
-    else:
-        steps_fn = [hp.prepare_step(hb, g, o, w.lr, presort=presort) for hb, g, o in zip(batches, gouts, outs)]
+    steps_fn, presort = hp.prepare_steps(batches, gouts, outs, w.lr, presort=args.presort, single_stream=args.graph)
 
     # accounting per batch: lookups, bags, distinct rows
     acct = []

@@ -112,7 +112,9 @@ int32_t fae_sync(fae_ctx *ctx);
  * rows in flight per lane group, second form only), ("reduce_wg_waves", 0=auto (1)/1/2/4
  * waves per workgroup of the reduce kernel), ("fixup_variant", 0=auto: runs that
  * cross the reduce kernel's spans are finished inside it, 1=by a kernel of their own),
- * ("fwd_stream_out", 0/1). */
+ * ("fwd_stream_out", 0/1), ("handoff_fences", 0=the sums that one workgroup of the reduce kernel
+ * hands to another are written and read with device-scope accesses and ordered by a wave-level
+ * fence, 1=they are bracketed by device-scope release/acquire fences as well). */
 int32_t fae_set_option(fae_ctx *ctx, const char *name, int64_t value);
 
 /* ---- per-kernel timing (measurement aid; off by default) ---------------------- */
@@ -137,15 +139,22 @@ int32_t fae_set_option(fae_ctx *ctx, const char *name, int64_t value);
 #define FAE_K_SYNC_ROWS 15   /* hot rows <-> full tables                          */
 #define FAE_K_ESTIMATE 16    /* chunk counts of the sampled logger                */
 #define FAE_K_READ_PROBE 17  /* plain streaming read (read-only bandwidth ceiling)      */
-#define FAE_K_COUNT 18
+#define FAE_K_FILL_PROBE 18  /* plain streaming fill (write-only bandwidth ceiling)     */
+#define FAE_K_COUNT 19
 int32_t fae_timing_enable(fae_ctx *ctx, int32_t on);
 int32_t fae_timing_reset(fae_ctx *ctx);
 int32_t fae_timing_read(fae_ctx *ctx, int32_t kernel_class, double *h_total_ms, int64_t *h_launches);
 const char *fae_kernel_name(int32_t kernel_class);
 /* Plain device-to-device streaming copy of `bytes` (multiple of 16) by a 16-byte-per-lane
  * kernel: what a bandwidth-bound kernel can reach on this device, and a transfer of known
- * size against which hardware byte counters are scaled.  Asynchronous. */
+ * size against which hardware byte counters are scaled.  The three probes take their launch
+ * shape from the options ("probe_unroll", 0=best known, 1/2/4/8 accesses in flight per lane),
+ * ("probe_nt", -1=best known, 0/1 non-temporal accesses) and ("probe_wgs_per_cu", 0=one
+ * workgroup of 256 lanes per chunk of unroll*256 vectors, n=n workgroups per compute unit
+ * striding over the chunks).  Asynchronous. */
 int32_t fae_copy_probe(fae_ctx *ctx, void *dst, const void *src, size_t bytes);
+/* The same, writing only: `bytes` of dst are set to `value`. */
+int32_t fae_fill_probe(fae_ctx *ctx, void *dst, size_t bytes, float value);
 /* The same access pattern, reading only: `bytes` (multiple of 16) of src are loaded and
  * summed; nothing is stored unless the sum has one particular value, in which case one float
  * goes to sink[0] (so the loads cannot be dropped).  What a read-dominated kernel can reach
@@ -229,8 +238,10 @@ size_t fae_bwd_workspace_bytes(const fae_tables *hot_tables, int64_t n_samples,
  * main stream between this call and fae_embbag_bwd_sgd (the forward, the dense layers).
  * It starts after all work queued on the main stream so far.  A following
  * fae_embbag_bwd_sgd with the same batch and workspace waits for it and skips its own
- * sort; with another batch in that workspace it waits and sorts itself.  The batch and the
- * workspace must stay untouched in between.  Sorted pairs are remembered per workspace, for
+ * sort; with another batch in that workspace it waits and sorts itself.  "The same batch" means
+ * the same index buffer, offset buffer and number of lookups for every table and the same
+ * number of samples; the contents of those buffers and of the workspace must stay untouched in
+ * between.  Sorted pairs are remembered per workspace, for
  * up to four workspaces at a time (beyond that the oldest are forgotten and their backward
  * call sorts again), so the next batch can be sorted into a second workspace while this
  * batch's forward and backward still run.  Asynchronous. */

@@ -24,7 +24,7 @@ FAE_OPT_SGD, FAE_OPT_ROWWISE_ADAGRAD = 0, 1
 
 EXPORTS = [
     "fae_create", "fae_destroy", "fae_last_error", "fae_version", "fae_sync", "fae_set_option",
-    "fae_timing_enable", "fae_timing_reset", "fae_timing_read", "fae_kernel_name", "fae_copy_probe", "fae_read_probe",
+    "fae_timing_enable", "fae_timing_reset", "fae_timing_read", "fae_kernel_name", "fae_copy_probe", "fae_read_probe", "fae_fill_probe",
     "fae_profile", "fae_choose_cutoff_workspace_bytes", "fae_choose_cutoff", "fae_count_hot",
     "fae_build_workspace_bytes", "fae_build_hot_tables", "fae_partition_workspace_bytes",
     "fae_partition_batch", "fae_embbag_fwd", "fae_bwd_workspace_bytes", "fae_embbag_bwd_presort",
@@ -214,7 +214,7 @@ def fae_set_option(ctx: Context, name: str, value: int):
     ctx.check(load().fae_set_option(ctx._h, name.encode(), C.c_int64(value)))
 
 
-FAE_K_COUNT = 18
+FAE_K_COUNT = 19
 
 
 def fae_kernel_name(kernel_class: int) -> str:
@@ -245,6 +245,11 @@ def fae_copy_probe(ctx: Context, dst: torch.Tensor, src: torch.Tensor):
 def fae_read_probe(ctx: Context, src: torch.Tensor, sink: torch.Tensor):
     ctx.check(load().fae_read_probe(ctx._h, C.c_void_p(src.data_ptr()), C.c_size_t(src.numel() * src.element_size()),
                                     _ptr(sink, torch.float32)))
+
+
+def fae_fill_probe(ctx: Context, dst: torch.Tensor, value: float = 0.0):
+    ctx.check(load().fae_fill_probe(ctx._h, C.c_void_p(dst.data_ptr()), C.c_size_t(dst.numel() * dst.element_size()),
+                                    C.c_float(value)))
 
 
 def fae_profile(ctx: Context, tables: Tables, chunk: Batch, counts: List[torch.Tensor]):

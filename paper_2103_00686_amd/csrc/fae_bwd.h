@@ -54,6 +54,7 @@ struct BwdArgs {
     int32_t *flags;    // [n_flags] one word per span: its border sums are published (zeroed by the sort stage)
     int32_t n_flags;
     int32_t fused_fixup; // border-crossing runs are finished inside the reduce kernel
+    int32_t handoff;     // how border sums pass between workgroups: 0 device-scope accesses + wave-level ordering, 1 device-scope fences
     int32_t wg_waves;    // waves (spans) per workgroup of the reduce kernel: 1, 2 or 4
     int32_t form;        // reduce kernel: 0 scan across the lane groups, 1 a share of the span per lane group
     int32_t span;      // lookups per wave in the reduce kernel

@@ -247,8 +247,7 @@ static int32_t bwd_impl(fae_ctx *ctx, const fae_tables *hot_tables, float *const
         // whatever the side stream was asked to do in this workspace must be finished before it is used
         FAE_HIP(ctx, hipStreamWaitEvent(ctx->stream, ps->ev_join, 0));
     }
-    if (ps && ps->first_indices == hot_batch->h_indices[0] && ps->n_samples == hot_batch->n_samples &&
-        ps->n_lookups == plan.N) {
+    if (ps && fae_ctx::presort_is(ps, nt, hot_batch)) {
         cur = ps->cur;
     } else {
         rc = bwd_sort_stage(ctx, ctx->stream, hot_tables, hot_batch, su, &cur);
@@ -285,6 +284,7 @@ static int32_t bwd_impl(fae_ctx *ctx, const fae_tables *hot_tables, float *const
             bwd_walk_fits(hot_tables, hot_batch, gout_row_stride, vec, ncols, lpr))
             a.form = 1;
         a.fused_fixup = ctx->opt_fixup != 1 && ncols <= lpr && spans <= a.n_flags;
+        a.handoff = ctx->opt_handoff == 1 ? 1 : 0;
         bwd_launch_reduce(ctx, a, vec, lpr);
         FAE_LAUNCH_CHECK(ctx);
     }

@@ -110,8 +110,22 @@ __device__ __forceinline__ SpanInfo bwd_span_info(const BwdArgs &a, int sid, int
 // Runs that cross span borders are finished by the span in which they end: it adds the pieces
 // the earlier spans have published (their tail sum where the run began, their whole-span sums in
 // between) to its own head sum and applies the update.  It only ever waits for spans with smaller
-// numbers, which were started before it; the wait is bounded all the same.  Called by every wave
-// once its own border sums have been stored with bwd_store_shared.
+// numbers, which the hardware starts first (workgroups are dispatched in the order of their
+// numbers; fixup_variant=1 finishes these runs in a kernel of its own and needs no such order);
+// the wait is bounded all the same, and a wave whose wait gives up sets the status word and
+// leaves the row alone.  Called by every wave once its own border sums have been stored with
+// bwd_store_shared.
+//
+// How the border sums reach the other workgroup (a.handoff):
+//   0  every word of a border sum is stored, and later loaded, with a device-scope access (it
+//      goes past the caches that belong to one part of the chip); the publishing wave waits
+//      for its stores to be acknowledged (a wave-level release fence: all outstanding memory
+//      operations of the wave, and no reordering by the compiler) and only then raises its flag;
+//      the reader loads the sums only after it has seen the flag.
+//   1  the same accesses, bracketed by device-scope fences as the memory model spells it out:
+//      release (write back this part's cache) before the flag is raised, acquire (drop this
+//      part's cached copies) after it has been seen.  On a chip whose second-level caches are
+//      per part these fences work on the whole cache, not on the few rows that matter.
 template <typename V, int LPR>
 __device__ __forceinline__ void bwd_finish_borders(const BwdArgs &a, const SpanInfo &sp, int sid, int n_hot, V *W,
                                                    V *part, int ncols)
@@ -121,7 +135,12 @@ __device__ __forceinline__ void bwd_finish_borders(const BwdArgs &a, const SpanI
     const int c = l; // one column slice per lane: the host takes this path only when the row fits LPR lanes
     const bool active = c < ncols;
     if (sp.head_open || sp.tail_open) {
-        __builtin_amdgcn_s_waitcnt(0x0F70); // vmcnt(0): this wave's border sums have been written
+        if (a.handoff == 1)
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+        else
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_s_waitcnt(0x0F70); // vmcnt(0): every lane's border sums have been acknowledged
+        __builtin_amdgcn_wave_barrier();
         if (lane == 0)
             __hip_atomic_store(&a.flags[sid], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
@@ -151,6 +170,7 @@ __device__ __forceinline__ void bwd_finish_borders(const BwdArgs &a, const SpanI
     // pieces 0 .. n_back-1: whole-span sums of spans sid-1-t; piece n_back: tail sum of the span the run began in
     V acc = bwd_vec<V>::zero();
     constexpr int PB = 4; // pieces whose flags, then whose rows, are fetched together
+    bool gave_up = false;
     for (int t0 = g; t0 <= n_back; t0 += PB * G) {
         int spins = 0;
         for (;;) { // until the pieces of this round are all published
@@ -168,10 +188,17 @@ __device__ __forceinline__ void bwd_finish_borders(const BwdArgs &a, const SpanI
                 break;
             if (++spins > SWEEP_SPIN_LIMIT) {
                 fae_flag(a.status, FAE_STATUS_EINTERNAL);
+                gave_up = true;
                 break;
             }
             __builtin_amdgcn_s_sleep(1);
         }
+        if (gave_up)
+            break;
+        if (a.handoff == 1)
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+        else
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
         V v[PB];
 #pragma unroll
         for (int q = 0; q < PB; ++q) {
@@ -186,6 +213,10 @@ __device__ __forceinline__ void bwd_finish_borders(const BwdArgs &a, const SpanI
         for (int q = 0; q < PB; ++q)
             bwd_vec<V>::add(acc, v[q]);
     }
+    // a wait that gave up in any lane group: the row (and its accumulator) stays as it was; the
+    // status word makes the next synchronising call report the step as invalid
+    if (__ballot(gave_up) != 0)
+        return;
 #pragma unroll
     for (int mm = LPR; mm < FAE_WAVE; mm <<= 1) {
         const V o = bwd_shfl<V>(acc, lane ^ mm);
@@ -221,7 +252,11 @@ template <typename V, int LPR> __global__ __launch_bounds__(256) void bwd_reduce
     const int z_of_span = fae_find_table(a.blk_start, a.n_tables, sid);
     if (sid >= a.n_spans)
         return;
+    // a bounded wait of the sort stage gave up: the pairs are not what they should be
+    const uint32_t status = __hip_atomic_load(a.status + FAE_BLK_STATUS, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     const SpanInfo sp = bwd_span_info(a, sid, z_of_span);
+    if (status & FAE_STATUS_EINTERNAL)
+        return;
     const int lane = fae_lane(), g = lane / LPR, l = lane % LPR;
     const int ncols = a.dim / VW;
     const int n_hot = a.n_hot[sp.z];
@@ -371,7 +406,11 @@ template <int LPR, int NB> __global__ __launch_bounds__(256) void bwd_reduce_wal
     const int z_of_span = fae_find_table(a.blk_start, a.n_tables, sid);
     if (sid >= a.n_spans)
         return;
+    // a bounded wait of the sort stage gave up: the pairs are not what they should be
+    const uint32_t status = __hip_atomic_load(a.status + FAE_BLK_STATUS, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     const SpanInfo sp = bwd_span_info(a, sid, z_of_span);
+    if (status & FAE_STATUS_EINTERNAL)
+        return;
     const int lane = fae_lane(), g = lane / LPR, l = lane % LPR;
     const int ncols = a.dim / 4;
     const int n_hot = a.n_hot[sp.z];

@@ -257,6 +257,9 @@ template <bool CHAINED, int ITEMS> __global__ __launch_bounds__(SORT_THREADS) vo
     __shared__ int skey[TILE], sval[TILE];
     __shared__ int scan_lds[SORT_THREADS / FAE_WAVE + 1];
     __shared__ int s_tile;
+    __shared__ int s_gave_up; // a chained wait of this tile gave up: nothing of the tile is written
+    if (CHAINED && threadIdx.x == 0)
+        s_gave_up = 0;
     int tile = blockIdx.x;
     if (CHAINED && a.use_ticket) {
         if (threadIdx.x == 0)
@@ -348,6 +351,7 @@ template <bool CHAINED, int ITEMS> __global__ __launch_bounds__(SORT_THREADS) vo
                         if (flag == 0) { // not published yet: start the next round at this tile
                             if (++spins > SWEEP_SPIN_LIMIT) {
                                 fae_flag(a.status, FAE_STATUS_EINTERNAL);
+                                s_gave_up = 1;
                                 done = true;
                             } else {
                                 __builtin_amdgcn_s_sleep(1);
@@ -377,6 +381,11 @@ template <bool CHAINED, int ITEMS> __global__ __launch_bounds__(SORT_THREADS) vo
         wcnt[3][t] = tb + c0 + c1 + c2;
     }
     __syncthreads();
+    // The running total of a tile whose wait gave up is wrong (it was published all the same, so
+    // that later tiles do not wait in turn): its pairs are not written.  The status word is set;
+    // the reduce kernel looks at it before it reads any pair and leaves the tables alone.
+    if (CHAINED && s_gave_up)
+        return;
 #pragma unroll
     for (int i = 0; i < ITEMS; ++i) {
         if (base + i * FAE_WAVE + lane < seg1) {
@@ -668,9 +677,7 @@ extern "C" int32_t fae_embbag_bwd_presort(fae_ctx *ctx, const fae_tables *hot_ta
     ps->valid = true;
     ps->side = true;
     ps->ws = ws;
-    ps->first_indices = hot_batch->h_indices[0];
-    ps->n_samples = hot_batch->n_samples;
-    ps->n_lookups = su.plan.N;
+    fae_ctx::presort_bind(ps, hot_tables->n_tables, hot_batch);
     ps->cur = cur;
     ps->age = ++ctx->presort_clock;
     return FAE_OK;
@@ -794,9 +801,7 @@ extern "C" int32_t fae_embbag_fwd_presort(fae_ctx *ctx, const fae_tables *hot_ta
     ps->valid = true;
     ps->side = false;
     ps->ws = ws;
-    ps->first_indices = hot_batch->h_indices[0];
-    ps->n_samples = hot_batch->n_samples;
-    ps->n_lookups = su.plan.N;
+    fae_ctx::presort_bind(ps, nt, hot_batch);
     ps->cur = 0;
     ps->age = ++ctx->presort_clock;
     return FAE_OK;

@@ -214,7 +214,8 @@ extern "C" const char *fae_kernel_name(int32_t k)
     static const char *names[FAE_K_COUNT] = {"fwd",        "bwd_keys",  "sort_hist", "sort_colscan", "sort_scatter",
                                              "bwd_reduce", "bwd_fixup", "lds_sort",  "fill",         "profile",
                                              "partition",  "build",     "other",     "copy_probe",
-                                             "fwd_sort",   "sync_rows", "estimate",  "read_probe"};
+                                             "fwd_sort",   "sync_rows", "estimate",  "read_probe",
+                                             "fill_probe"};
     return (k >= 0 && k < FAE_K_COUNT) ? names[k] : "?";
 }
 
@@ -246,6 +247,14 @@ extern "C" int32_t fae_set_option(fae_ctx *ctx, const char *name, int64_t value)
         ctx->opt_wg_waves = value;
     else if (!strcmp(name, "reduce_unroll") && (value == 0 || value == 4 || value == 8))
         ctx->opt_unroll = value;
+    else if (!strcmp(name, "handoff_fences") && value >= 0 && value <= 1)
+        ctx->opt_handoff = value;
+    else if (!strcmp(name, "probe_unroll") && (value == 0 || value == 1 || value == 2 || value == 4 || value == 8))
+        ctx->opt_probe_unroll = value;
+    else if (!strcmp(name, "probe_nt") && value >= -1 && value <= 1)
+        ctx->opt_probe_nt = value;
+    else if (!strcmp(name, "probe_wgs_per_cu") && value >= 0 && value <= 64)
+        ctx->opt_probe_wgs_per_cu = value;
     else
         return fae_fail(ctx, FAE_EINVAL, "fae_set_option: unknown option or value: %s=%lld", name,
                         (long long)value);

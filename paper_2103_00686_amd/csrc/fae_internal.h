@@ -43,6 +43,11 @@ struct fae_ctx {
     int64_t opt_reduce = 0;     // reduce kernel: 0 auto, 1 scan across lane groups, 2 a share of the span per lane group
     int64_t opt_wg_waves = 0;   // reduce kernel: waves per workgroup (0 = auto, 1, 2, 4)
     int64_t opt_unroll = 0;     // gradient rows in flight per lane group in the second form (0 = auto, 4, 8)
+    int64_t opt_handoff = 0;    // border sums between workgroups: 0 auto (device-scope accesses, wave-level ordering), 1 device-scope fences
+    // launch shape of the streaming probes (0 / -1: the shape that measured best)
+    int64_t opt_probe_unroll = 0;      // 16-byte accesses in flight per lane: 1, 2, 4, 8
+    int64_t opt_probe_nt = -1;         // non-temporal accesses: 0, 1
+    int64_t opt_probe_wgs_per_cu = 0;  // 0: one workgroup per chunk; n: n workgroups per compute unit striding over the chunks
     char err[512] = {0};
     // side stream for work that may overlap the main stream (backward presort)
     // two of them, taken in turn: the sorts of consecutive batches may overlap each other
@@ -57,8 +62,12 @@ struct fae_ctx {
         bool valid = false;
         bool side = false; // sorted on the side stream (needs the join event) or on the main stream
         const void *ws = nullptr;
-        const void *first_indices = nullptr;
-        int64_t n_samples = 0, n_lookups = 0;
+        // the batch the pairs were sorted from: every table's index and offset buffers and its lookups
+        int n_tables = 0;
+        const void *indices[FAE_MAX_TABLES] = {nullptr};
+        const void *offsets[FAE_MAX_TABLES] = {nullptr};
+        int64_t n_lookups_z[FAE_MAX_TABLES] = {0};
+        int64_t n_samples = 0;
         int cur = 0;
         uint64_t age = 0;
         hipEvent_t ev_join = nullptr;
@@ -83,6 +92,30 @@ struct fae_ctx {
             if (e.valid && e.ws == ws)
                 return &e;
         return nullptr;
+    }
+    // Remember which batch the pairs in e's workspace belong to / ask whether b is that batch.  A
+    // batch is known by the buffers it names: the same pointers and sizes for every table.  (A
+    // caller that rewrites a buffer in place between the sort and the backward is outside what
+    // the pointers can tell: the batch and the workspace must stay untouched in between.)
+    static void presort_bind(Presort *e, int nt, const fae_batch *b)
+    {
+        e->n_tables = nt;
+        e->n_samples = b->n_samples;
+        for (int z = 0; z < nt; ++z) {
+            e->indices[z] = b->h_indices[z];
+            e->offsets[z] = b->h_offsets ? b->h_offsets[z] : nullptr;
+            e->n_lookups_z[z] = b->h_n_lookups[z];
+        }
+    }
+    static bool presort_is(const Presort *e, int nt, const fae_batch *b)
+    {
+        if (e->n_tables != nt || e->n_samples != b->n_samples)
+            return false;
+        for (int z = 0; z < nt; ++z)
+            if (e->indices[z] != b->h_indices[z] || e->offsets[z] != (b->h_offsets ? b->h_offsets[z] : nullptr) ||
+                e->n_lookups_z[z] != b->h_n_lookups[z])
+                return false;
+        return true;
     }
     // per-kernel timing
     bool timing = false;

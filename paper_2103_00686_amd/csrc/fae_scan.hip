@@ -45,44 +45,120 @@ __global__ __launch_bounds__(256) void fae_fill_kernel(uint32_t *p, int64_t n, u
         p[i] = v;
 }
 
-__global__ __launch_bounds__(256) void fae_copy_probe_kernel(float4 *dst, const float4 *src, int64_t n)
+// ---------------------------------------------------------------------------------
+// Plain streaming kernels: what a bandwidth-bound kernel reaches on this device, and
+// transfers of known size against which hardware byte counters are scaled.  16 bytes
+// per lane and access; a workgroup of 256 lanes owns chunks of U * 256 consecutive
+// vectors (U accesses in flight per lane).  The grid is either one workgroup per chunk
+// (the default: the dispatcher hands out short workgroups as fast as they retire,
+// which measured best here) or a fixed number of workgroups per compute unit that
+// stride over the chunks.  NT: non-temporal loads / stores.
+// ---------------------------------------------------------------------------------
+typedef float fae_probe_v4 __attribute__((ext_vector_type(4)));
+
+template <int NT> __device__ __forceinline__ fae_probe_v4 probe_load(const fae_probe_v4 *p)
 {
-    // four independent 16-byte loads per lane in flight, then four stores
-    const int64_t stride = (int64_t)gridDim.x * 256;
-    int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    for (; i + 3 * stride < n; i += 4 * stride) {
-        const float4 a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
-        dst[i] = a;
-        dst[i + stride] = b;
-        dst[i + 2 * stride] = c;
-        dst[i + 3 * stride] = d;
-    }
-    for (; i < n; i += stride)
-        dst[i] = src[i];
+    if (NT)
+        return __builtin_nontemporal_load(p);
+    return *p;
+}
+template <int NT> __device__ __forceinline__ void probe_store(fae_probe_v4 *p, const fae_probe_v4 &v)
+{
+    if (NT)
+        __builtin_nontemporal_store(v, p);
+    else
+        *p = v;
 }
 
-__global__ __launch_bounds__(256) void fae_read_probe_kernel(const float4 *src, int64_t n, float *sink)
+template <int U, int NT>
+__global__ __launch_bounds__(256) void fae_copy_probe_kernel(fae_probe_v4 *dst, const fae_probe_v4 *src, int64_t n)
 {
-    const int64_t stride = (int64_t)gridDim.x * 256;
-    int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
-    for (; i + 3 * stride < n; i += 4 * stride) {
-        const float4 a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
-        s.x += (a.x + b.x) + (c.x + d.x);
-        s.y += (a.y + b.y) + (c.y + d.y);
-        s.z += (a.z + b.z) + (c.z + d.z);
-        s.w += (a.w + b.w) + (c.w + d.w);
+    const int64_t chunk = (int64_t)U * 256;
+    for (int64_t base = (int64_t)blockIdx.x * chunk; base < n; base += (int64_t)gridDim.x * chunk) {
+        fae_probe_v4 v[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t i = base + u * 256 + threadIdx.x;
+            if (i < n)
+                v[u] = probe_load<NT>(src + i);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t i = base + u * 256 + threadIdx.x;
+            if (i < n)
+                probe_store<NT>(dst + i, v[u]);
+        }
     }
-    for (; i < n; i += stride) {
-        const float4 a = src[i];
-        s.x += a.x;
-        s.y += a.y;
-        s.z += a.z;
-        s.w += a.w;
+}
+
+template <int U, int NT>
+__global__ __launch_bounds__(256) void fae_read_probe_kernel(const fae_probe_v4 *src, int64_t n, float *sink)
+{
+    const int64_t chunk = (int64_t)U * 256;
+    fae_probe_v4 s = {0.f, 0.f, 0.f, 0.f};
+    for (int64_t base = (int64_t)blockIdx.x * chunk; base < n; base += (int64_t)gridDim.x * chunk) {
+        fae_probe_v4 v[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t i = base + u * 256 + threadIdx.x;
+            v[u] = i < n ? probe_load<NT>(src + i) : s * 0.f;
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            s += v[u];
     }
-    if ((s.x + s.y) + (s.z + s.w) == 1.2345678e-30f)
+    if ((s.x + s.y) + (s.z + s.w) == 1.2345678e-30f) // never, for the buffers this is run on: keeps the loads alive
         sink[0] = s.x;
 }
+
+template <int U, int NT> __global__ __launch_bounds__(256) void fae_fill_probe_kernel(fae_probe_v4 *dst, int64_t n, float val)
+{
+    const int64_t chunk = (int64_t)U * 256;
+    const fae_probe_v4 v = {val, val, val, val};
+    for (int64_t base = (int64_t)blockIdx.x * chunk; base < n; base += (int64_t)gridDim.x * chunk) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t i = base + u * 256 + threadIdx.x;
+            if (i < n)
+                probe_store<NT>(dst + i, v);
+        }
+    }
+}
+
+namespace {
+// the launch shape of a probe: the context's probe_* options, or the shape that measured best
+struct ProbeShape {
+    int unroll, nt;
+    unsigned grid;
+};
+ProbeShape probe_shape(const fae_ctx *ctx, int64_t n, int best_unroll, int best_nt)
+{
+    ProbeShape p;
+    p.unroll = ctx->opt_probe_unroll ? (int)ctx->opt_probe_unroll : best_unroll;
+    p.nt = ctx->opt_probe_nt >= 0 ? (int)ctx->opt_probe_nt : best_nt;
+    int64_t blocks = (n + (int64_t)p.unroll * 256 - 1) / ((int64_t)p.unroll * 256);
+    if (ctx->opt_probe_wgs_per_cu > 0 && blocks > ctx->opt_probe_wgs_per_cu * ctx->n_cu)
+        blocks = ctx->opt_probe_wgs_per_cu * ctx->n_cu;
+    if (blocks > 2147483647LL)
+        blocks = 2147483647LL; // the chunks beyond are reached by the stride
+    p.grid = (unsigned)blocks;
+    return p;
+}
+#define PROBE_DISPATCH(KERNEL, shape, ...)                                                                   \
+    do {                                                                                                     \
+        const dim3 g_((shape).grid), b_(256);                                                                \
+        switch ((shape).unroll * 2 + (shape).nt) {                                                           \
+        case 2: hipLaunchKernelGGL((KERNEL<1, 0>), g_, b_, 0, ctx->stream, __VA_ARGS__); break;              \
+        case 3: hipLaunchKernelGGL((KERNEL<1, 1>), g_, b_, 0, ctx->stream, __VA_ARGS__); break;              \
+        case 4: hipLaunchKernelGGL((KERNEL<2, 0>), g_, b_, 0, ctx->stream, __VA_ARGS__); break;              \
+        case 5: hipLaunchKernelGGL((KERNEL<2, 1>), g_, b_, 0, ctx->stream, __VA_ARGS__); break;              \
+        case 8: hipLaunchKernelGGL((KERNEL<4, 0>), g_, b_, 0, ctx->stream, __VA_ARGS__); break;              \
+        case 9: hipLaunchKernelGGL((KERNEL<4, 1>), g_, b_, 0, ctx->stream, __VA_ARGS__); break;              \
+        case 16: hipLaunchKernelGGL((KERNEL<8, 0>), g_, b_, 0, ctx->stream, __VA_ARGS__); break;             \
+        default: hipLaunchKernelGGL((KERNEL<8, 1>), g_, b_, 0, ctx->stream, __VA_ARGS__); break;             \
+        }                                                                                                    \
+    } while (0)
+} // namespace
 
 extern "C" int32_t fae_read_probe(fae_ctx *ctx, const void *src, size_t bytes, float *sink)
 {
@@ -91,13 +167,9 @@ extern "C" int32_t fae_read_probe(fae_ctx *ctx, const void *src, size_t bytes, f
     const int64_t n = (int64_t)(bytes / 16);
     if (n == 0)
         return FAE_OK;
-    int64_t blocks = (n + 255) / 256;
-    const int64_t cap = (int64_t)ctx->n_cu * 32;
-    if (blocks > cap)
-        blocks = cap;
+    const ProbeShape shape = probe_shape(ctx, n, 4, 1);
     fae_ktimer kt(ctx, FAE_K_READ_PROBE);
-    hipLaunchKernelGGL(fae_read_probe_kernel, dim3((unsigned)blocks), dim3(256), 0, ctx->stream, (const float4 *)src, n,
-                       sink);
+    PROBE_DISPATCH(fae_read_probe_kernel, shape, (const fae_probe_v4 *)src, n, sink);
     FAE_LAUNCH_CHECK(ctx);
     return FAE_OK;
 }
@@ -109,13 +181,23 @@ extern "C" int32_t fae_copy_probe(fae_ctx *ctx, void *dst, const void *src, size
     const int64_t n = (int64_t)(bytes / 16);
     if (n == 0)
         return FAE_OK;
-    int64_t blocks = (n + 255) / 256;
-    const int64_t cap = (int64_t)ctx->n_cu * 32; // grid-stride: a few waves per SIMD, many vectors per lane
-    if (blocks > cap)
-        blocks = cap;
+    const ProbeShape shape = probe_shape(ctx, n, 1, 0);
     fae_ktimer kt(ctx, FAE_K_COPY_PROBE);
-    hipLaunchKernelGGL(fae_copy_probe_kernel, dim3((unsigned)blocks), dim3(256), 0, ctx->stream, (float4 *)dst,
-                       (const float4 *)src, n);
+    PROBE_DISPATCH(fae_copy_probe_kernel, shape, (fae_probe_v4 *)dst, (const fae_probe_v4 *)src, n);
+    FAE_LAUNCH_CHECK(ctx);
+    return FAE_OK;
+}
+
+extern "C" int32_t fae_fill_probe(fae_ctx *ctx, void *dst, size_t bytes, float value)
+{
+    if (!ctx || !dst || bytes % 16 != 0 || ((uintptr_t)dst) % 16 != 0)
+        return fae_fail(ctx, FAE_EINVAL, "fae_fill_probe: null or misaligned argument");
+    const int64_t n = (int64_t)(bytes / 16);
+    if (n == 0)
+        return FAE_OK;
+    const ProbeShape shape = probe_shape(ctx, n, 1, 0);
+    fae_ktimer kt(ctx, FAE_K_FILL_PROBE);
+    PROBE_DISPATCH(fae_fill_probe_kernel, shape, (fae_probe_v4 *)dst, n, value);
     FAE_LAUNCH_CHECK(ctx);
     return FAE_OK;
 }

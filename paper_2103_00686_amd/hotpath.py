@@ -147,6 +147,23 @@ class HotPath:
             return step
         return [make(i) for i in range(n)]
 
+    def prepare_steps(self, hbs: Sequence[HotBatch], gouts: Sequence[torch.Tensor], outs: Sequence[torch.Tensor],
+                      lr: float, presort: str = "auto", single_stream: bool = False):
+        """The training steps of a cycle of hot batches as zero-argument callables (to be called in
+        cyclic order), and the name of the call sequence they use.  presort "auto" picks, from the
+        shapes alone: "fused" (forward and the backward's sort in one launch) when every table is
+        one-hot and the batches have at most 16384 samples; "ahead" (the next batch's sort on the
+        side stream beside this batch's forward and backward) for other steps of up to 4 M lookups,
+        whose sort is a string of short launches; else the calls one after the other ("fused", which
+        is the plain forward for such shapes).  single_stream rules "ahead" out (graph capture)."""
+        if presort == "auto":
+            fusable = all(o is None for hb in hbs for o in hb.offsets) and max(hb.n_samples for hb in hbs) <= 16384
+            short_sort = max(sum(hb.n_lookups) for hb in hbs) <= (1 << 22)
+            presort = "ahead" if (not fusable and short_sort and not single_stream) else "fused"
+        if presort == "ahead":
+            return self.prepare_pipeline(hbs, gouts, outs, lr), presort
+        return [self.prepare_step(hb, g, o, lr, presort=presort) for hb, g, o in zip(hbs, gouts, outs)], presort
+
     # -- a1 -------------------------------------------------------------------------
     def alloc_counts(self):
         """Access counters of every table, zeroed (profile() makes them on first use otherwise)."""

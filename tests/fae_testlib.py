@@ -203,6 +203,78 @@ class Pipeline:
                 self.wtol[z][uniq[z]] = (inh + RTOL * mg[z]).astype(np.float32) * np.float32(1.001)
 
 
+class SparseTables:
+    """The oracle's copy of hot tables that are too large to hold on the host: only rows that some
+    step has updated are kept (with the error bound they have inherited, see the module header);
+    every other row is the procedural initial weight W0(seed, table, row)."""
+
+    def __init__(self, seed: int, hot_ids: List[np.ndarray], dim: int):
+        self.seed, self.hot_ids, self.dim = seed, hot_ids, dim
+        nt = len(hot_ids)
+        self.slots = [np.empty(0, dtype=np.int64) for _ in range(nt)]
+        self.rows = [np.empty((0, dim), dtype=np.float32) for _ in range(nt)]
+        self.tol = [np.empty((0, dim), dtype=np.float32) for _ in range(nt)]
+
+    def fetch(self, z: int, want: np.ndarray):
+        """Current rows (and inherited bounds) of the ascending distinct slots `want` of table z."""
+        want = np.asarray(want, dtype=np.int64)
+        rows = O.w0_rows(self.seed, z, self.hot_ids[z][want].astype(np.int64), self.dim)
+        tol = np.zeros(rows.shape, dtype=np.float32)
+        have = self.slots[z]
+        if have.size and want.size:
+            pos = np.minimum(np.searchsorted(have, want), have.size - 1)
+            hit = have[pos] == want
+            rows[hit] = self.rows[z][pos[hit]]
+            tol[hit] = self.tol[z][pos[hit]]
+        return rows, tol
+
+    def store(self, z: int, slots: np.ndarray, rows: np.ndarray, tol: np.ndarray):
+        slots = np.asarray(slots, dtype=np.int64)
+        keep = ~np.isin(self.slots[z], slots)
+        all_slots = np.concatenate([self.slots[z][keep], slots])
+        order = np.argsort(all_slots, kind="stable")
+        self.slots[z] = all_slots[order]
+        self.rows[z] = np.concatenate([self.rows[z][keep], rows])[order]
+        self.tol[z] = np.concatenate([self.tol[z][keep], tol])[order]
+
+    def touched(self, z: int) -> np.ndarray:
+        return self.slots[z]
+
+
+def check_step_sparse(store: SparseTables, hp: HotPath, n_samples: int, slots: List[np.ndarray],
+                      offs: List[Optional[np.ndarray]], out: torch.Tensor, gout: torch.Tensor, lr: float, what: str,
+                      dbg=None):
+    """One step that the library has already taken on its own tables (any call sequence), against
+    the oracle, table by table and in full: every pooled row against the oracle's forward with the
+    weights before the step, every updated row against the oracle's update, and (when the library's
+    optional outputs are given) the distinct slots and their multiplicities bit for bit.  The oracle
+    works on the rows the batch touches, compacted; its tables advance with the step."""
+    dev = out.device
+    nt = len(slots)
+    for z in range(nt):
+        sl = np.asarray(slots[z], dtype=np.int32)
+        uniq_slots, inv = np.unique(sl, return_inverse=True)
+        inv = inv.astype(np.int32)
+        if uniq_slots.size == 0:
+            assert not bool(out[:, z, :].any()), f"{what}: table {z} has no lookups but a non-zero output"
+            continue
+        Wc, tolc = store.fetch(z, uniq_slots)
+        ref, mag = O.embbag_fwd([Wc], n_samples, [inv], [offs[z]], want_mag=True)
+        inherited = O.embbag_fwd([tolc], n_samples, [inv], [offs[z]]).astype(np.float64) * 1.001
+        got = out[:, z, :].cpu().numpy()
+        assert_close_sum(got, ref[:, 0, :], mag[:, 0, :], f"{what}: forward, table {z}", inherited[:, 0, :])
+        g_z = np.ascontiguousarray(gout[:, z:z + 1, :].cpu().numpy())
+        uniq, runlen, mg = O.embbag_bwd_sgd([Wc], n_samples, [inv], [offs[z]], g_z, lr, want_mag=True)
+        assert np.array_equal(uniq[0], np.arange(uniq_slots.size))      # every compacted row is touched
+        if dbg is not None:
+            assert np.array_equal(dbg[0][z].cpu().numpy(), uniq_slots), f"{what}: distinct slots of table {z} differ"
+            assert np.array_equal(dbg[1][z].cpu().numpy(), runlen[0]), f"{what}: multiplicities of table {z} differ"
+        got_rows = hp.hotW[z][torch.from_numpy(uniq_slots.astype(np.int64)).to(dev)].cpu().numpy()
+        assert_close_sum(got_rows, Wc, mg[0], f"{what}: updated rows, table {z}", tolc.astype(np.float64))
+        newtol = (tolc.astype(np.float64) + RTOL * mg[0]).astype(np.float32) * np.float32(1.001)
+        store.store(z, uniq_slots, Wc, newtol)
+
+
 def hot_batches(p: Pipeline, n_batches: int, stream0: int = 10) -> List[HotBatch]:
     """Hot-only mini-batches of the workload's batch size, the way the workload makes them:
     conditional-hot draws for multi-hot workloads, partition of a mixed stream otherwise."""

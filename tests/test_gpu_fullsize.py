@@ -2,9 +2,11 @@
 benchmark times (same tables, batch sizes, procedural weights, table-batched launches).
 
 Integer stages are compared in full and bit-exactly (histogram, cutoff, remap, hot ids,
-partition lists, slots, offsets, distinct-slot lists, multiplicities).  fp32 results are
-compared on sampled outputs the oracle computes one by one: pooled rows of sampled
-bags, updated rows of sampled runs (the longest runs always included), untouched rows.
+partition lists, slots, offsets, distinct-slot lists, multiplicities).  The training steps
+go through the call sequences the benchmark times (three steps in a row, then one through
+the plain calls) and are compared in full as well: every pooled row and every updated row
+of every step against the oracle, which works on the rows a batch touches; rows that no
+step touched are sampled and must keep their initial bits.
 Every oracle input comes from the seeded generators or from the oracle itself; the
 hot batches are built from the ORACLE's remap, never from the library's.
 """
@@ -108,72 +110,64 @@ def test_full_size_workload(cfg_id):
         assert np.array_equal(hp.last_hoffsets[z].cpu().numpy(), hoff[z]), f"offsets of table {z} differ"
     _log(f"partition ok: {hs.size} hot of {n_mix}")
 
-    # ---- one hot mini-batch of the workload's size, built from the oracle's outputs ----------
+    # ---- hot mini-batches of the workload's size, built from the oracle's outputs --------------
+    N_STEPS = 3
+    hbs, np_slots, np_offs = [], [], []
     if w.conditional_hot:
         remap_dev = [torch.from_numpy(r).to(dev) for r in remap]
-        ch = S.make_chunk(w, 11, 0, w.batch, device=dev, hot_remap=remap_dev)
-        idx = [i.cpu().numpy() for i in ch.indices]
-        off = [None if o is None else o.cpu().numpy() for o in ch.offsets]
-        hs, cs, slots, hoff = O.partition(w.rows, w.batch, idx, off, remap)
-        assert hs.size == w.batch
+        for k in range(N_STEPS):
+            ch = S.make_chunk(w, 11 + k, 0, w.batch, device=dev, hot_remap=remap_dev)
+            idx = [i.cpu().numpy() for i in ch.indices]
+            off = [None if o is None else o.cpu().numpy() for o in ch.offsets]
+            hs_k, cs_k, slots_k, hoff_k = O.partition(w.rows, w.batch, idx, off, remap)
+            assert hs_k.size == w.batch
+            np_slots.append(slots_k)
+            np_offs.append([None if w.bag_kinds[z] == "one" else hoff_k[z].astype(np.int32) for z in range(nt)])
+            del ch
         del remap_dev
     else:
-        assert hs.size >= w.batch, "not enough hot samples in the mixed chunk"
-        slots = [s[:w.batch].copy() for s in slots]          # one-hot: first `batch` hot samples
-        hoff = [h[:w.batch + 1] for h in hoff]
-    offs = [None if w.bag_kinds[z] == "one" else hoff[z].astype(np.int32) for z in range(nt)]
-    hb = HotBatch(w.batch, [torch.from_numpy(s).to(dev) for s in slots],
-                  [None if o is None else torch.from_numpy(o).to(dev) for o in offs], [s.size for s in slots])
-    NL = sum(hb.n_lookups)
-    _log(f"hot batch: {w.batch} samples, {NL} lookups")
+        assert hs.size >= N_STEPS * w.batch, "not enough hot samples in the mixed chunk"
+        for k in range(N_STEPS):     # one-hot: consecutive slices of the hot list
+            np_slots.append([s[k * w.batch:(k + 1) * w.batch].copy() for s in slots])
+            np_offs.append([None] * nt)
+    for sl, of in zip(np_slots, np_offs):
+        hbs.append(HotBatch(w.batch, [torch.from_numpy(s).to(dev) for s in sl],
+                            [None if o is None else torch.from_numpy(o).to(dev) for o in of], [s.size for s in sl]))
+    _log(f"{N_STEPS} hot batches: {w.batch} samples, {[sum(hb.n_lookups) for hb in hbs]} lookups")
 
-    # ---- a6: forward, sampled bags ---------------------------------------------------------------
-    out = hp.forward(hb)
-    hp.sync()
-    n_bags = 1024
-    for z in range(nt):
-        pick = np.unique(rng.integers(0, w.batch, n_bags))
-        lo = pick if offs[z] is None else offs[z][pick]
-        hi = pick + 1 if offs[z] is None else offs[z][pick + 1]
-        lens = (hi - lo).astype(np.int64)
-        sub_slots = np.concatenate([slots[z][a:b] for a, b in zip(lo, hi)]) if lens.sum() else np.zeros(0, np.int32)
-        uniq, inv = np.unique(sub_slots, return_inverse=True)
-        Wc = O.w0_rows(w.seed, z, hot_ids[z][uniq].astype(np.int64), D) if uniq.size else np.zeros((1, D), np.float32)
-        sub_off = np.zeros(pick.size + 1, dtype=np.int32)
-        sub_off[1:] = np.cumsum(lens)
-        ref, mag = O.embbag_fwd([Wc], pick.size, [inv.astype(np.int32)], [sub_off], want_mag=True)
-        got = out[torch.from_numpy(pick).to(dev), z, :].cpu().numpy()
-        T.assert_close_sum(got, ref[:, 0, :], mag[:, 0, :], f"forward, table {z}")
-        one = lens <= 1
-        assert got[one].tobytes() == ref[one, 0, :].tobytes()     # no arithmetic: bit-exact
-    _log("forward ok")
+    # ---- a6 + a7 + a8 through the calls the benchmark times, three steps in a row ------------------
+    # (fused forward + sort launch then backward on workloads 2 and 3, sort one step ahead on the side
+    # stream on workload 4, the plain calls on workload 5).  Every step is compared in full: all pooled
+    # rows, all updated rows; step 3 re-reads rows that steps 1 and 2 wrote.
+    store = T.SparseTables(w.seed, hot_ids, D)
+    gouts = [S.upstream_grads(w, 21 + k, w.batch, device=dev) for k in range(N_STEPS)]
+    outs = [torch.empty((w.batch, nt, D), dtype=torch.float32, device=dev) for _ in range(N_STEPS)]
+    steps, mode = hp.prepare_steps(hbs, gouts, outs, w.lr)
+    assert mode == {2: "fused", 3: "fused", 4: "ahead", 5: "fused"}[cfg_id]
+    for k in range(N_STEPS):
+        outs[k].fill_(float("nan"))
+        steps[k]()
+        hp.sync()
+        T.check_step_sparse(store, hp, w.batch, np_slots[k], np_offs[k], outs[k], gouts[k], w.lr, f"step {k + 1} ({mode})")
+        _log(f"step {k + 1} through the benchmark's calls ({mode}) ok")
 
-    # ---- a7 + a8: backward + SGD; run lists in full, updated rows sampled ------------------------
-    gout = S.upstream_grads(w, 21, w.batch, device=dev)
-    dbg = hp.backward_sgd(hb, gout, w.lr, debug=True)
+    # ---- a fourth step through the plain calls, with the distinct-slot lists and multiplicities -----
+    g4 = S.upstream_grads(w, 31, w.batch, device=dev)
+    out4 = hp.forward(hbs[0])
+    dbg = hp.backward_sgd(hbs[0], g4, w.lr, debug=True)
     hp.sync()
-    g_cpu = gout.cpu().numpy()
+    T.check_step_sparse(store, hp, w.batch, np_slots[0], np_offs[0], out4, g4, w.lr, "step 4 (plain calls)", dbg=dbg)
+    # rows no step touched keep their initial bits
     for z in range(nt):
-        order, uniq, runlen = O.sort_runs(slots[z])
-        assert np.array_equal(dbg[0][z].cpu().numpy(), uniq), f"distinct slots of table {z} differ"
-        assert np.array_equal(dbg[1][z].cpu().numpy(), runlen), f"multiplicities of table {z} differ"
-        if uniq.size == 0:
+        if n_hot[z] == 0:
             continue
-        longest = np.argsort(runlen)[-16:]
-        sel = np.unique(np.concatenate([rng.integers(0, uniq.size, 1024), longest, [0, uniq.size - 1]]))
-        bag = O.bag_of(offs[z], w.batch, slots[z].size)
-        G, Ga = O.run_grads(order, bag, runlen, sel, g_cpu, z)
-        W0 = O.w0_rows(w.seed, z, hot_ids[z][uniq[sel]].astype(np.int64), D)
-        ref = O.sgd_rows(W0, G, w.lr)
-        got = hp.hotW[z][torch.from_numpy(uniq[sel].astype(np.int64)).to(dev)].cpu().numpy()
-        T.assert_close_sum(got, ref, np.abs(W0) + np.float64(np.float32(w.lr)) * Ga, f"updated rows, table {z}")
-        # rows no lookup touched keep their initial bits
         cand = rng.integers(0, n_hot[z], 4096)
-        cand = np.unique(cand[~np.isin(cand, uniq)])
+        cand = np.unique(cand[~np.isin(cand, store.touched(z))])
         if cand.size:
             got = hp.hotW[z][torch.from_numpy(cand).to(dev)].cpu().numpy()
             assert got.tobytes() == O.w0_rows(w.seed, z, hot_ids[z][cand].astype(np.int64), D).tobytes()
-    _log("backward + SGD ok")
+    _log("plain forward / backward + SGD ok; untouched rows unchanged")
+    del store, gouts, outs, steps, hbs, out4, g4
 
     # ---- embedding synchronisation with full tables that fit the device (Sec. 3 (4), Sec. 6.2) ---
     if sum(w.rows) * D * 4 <= (40 << 30):

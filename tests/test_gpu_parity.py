@@ -521,8 +521,12 @@ def test_step_replays_in_a_hip_graph(dev, one_hot):
     rgout = torch.zeros_like(gout)
     rout = torch.zeros_like(out)
     rstep = ref.prepare_step(hb, rgout, rout, lr, presort="none")
+    # the oracle takes the same four steps on its own copy of the tables
+    Wo = [x.copy() for x in W0]
+    wtol = [np.zeros_like(x) for x in W0]                # bound inherited from the earlier steps, per element
     for rep in range(4):
-        g = torch.from_numpy(rng.standard_normal((S_, 2, dim)).astype(np.float32)).to(dev)
+        g_np = rng.standard_normal((S_, 2, dim)).astype(np.float32)
+        g = torch.from_numpy(g_np).to(dev)
         gout.copy_(g)
         rgout.copy_(g)
         torch.cuda.synchronize()
@@ -534,6 +538,55 @@ def test_step_replays_in_a_hip_graph(dev, one_hot):
         assert torch.equal(out, rout), f"replay {rep}: pooled output differs"
         for z in range(2):
             assert torch.equal(hp.hotW[z], ref.hotW[z]), f"replay {rep}: table {z} differs"
+        # the eager twin (and with it the replay) against the oracle
+        o_ref, o_mag = O.embbag_fwd(Wo, S_, slots, offs, want_mag=True)
+        inherited = O.embbag_fwd(wtol, S_, slots, offs).astype(np.float64) * 1.001
+        T.assert_close_sum(rout.cpu().numpy(), o_ref, o_mag, f"replay {rep}: forward", inherited)
+        uniq, runlen, mag = O.embbag_bwd_sgd(Wo, S_, slots, offs, g_np, lr, want_mag=True)
+        for z in range(2):
+            got = ref.hotW[z].cpu().numpy()
+            touched = np.zeros(n_hot[z], dtype=bool)
+            touched[uniq[z]] = True
+            assert got[~touched].tobytes() == W0[z][~touched].tobytes(), f"replay {rep}: untouched rows of table {z} changed"
+            inh = wtol[z][uniq[z]].astype(np.float64)
+            T.assert_close_sum(got[uniq[z]], Wo[z][uniq[z]], mag[z], f"replay {rep}: updated rows of table {z}", inh)
+            wtol[z][uniq[z]] = (inh + T.RTOL * mag[z]).astype(np.float32) * np.float32(1.001)
         _ = (hp.hotW[0] * 2).sum().item()                # unrelated eager work between replays
-    # and the eager twin agrees with the oracle after the four steps (so both are right)
     assert not torch.equal(ref.hotW[0], torch.from_numpy(W0[0]).to(dev))
+
+
+def test_a_sorted_workspace_is_not_reused_for_another_batch(dev):
+    """Sorted pairs are remembered per workspace and reused only by the batch they were sorted from.
+    A batch that shares the first table's index buffer, the sample count and the lookup count with the
+    sorted one but names another buffer for the second table must be sorted afresh: the update equals
+    the oracle's for the batch that was passed, not for the one that was sorted."""
+    rng = np.random.default_rng(77)
+    dim, n_hot, S_, lr = 16, [500, 800], 1500, 0.1
+    W0 = [(rng.random((n, dim), dtype=np.float32) - 0.5) for n in n_hot]
+    s0 = rng.integers(0, n_hot[0], S_).astype(np.int32)
+    s1a = rng.integers(0, n_hot[1], S_).astype(np.int32)
+    s1b = rng.integers(0, n_hot[1], S_).astype(np.int32)
+    for fused in (False, True):
+        hp = HotPath(n_hot, dim, 0)
+        hp.n_hot = n_hot
+        hp.hotW = [torch.from_numpy(x.copy()).to(dev) for x in W0]
+        t0 = torch.from_numpy(s0).to(dev)
+        hb_a = HotBatch(S_, [t0, torch.from_numpy(s1a).to(dev)], [None, None], [S_, S_])
+        hb_b = HotBatch(S_, [t0, torch.from_numpy(s1b).to(dev)], [None, None], [S_, S_])
+        if fused:
+            hp.forward_presort(hb_a)          # leaves the sorted pairs of batch a in the workspace
+        else:
+            hp.presort(hb_a)                  # the same on the side stream
+        g_np = rng.standard_normal((S_, 2, dim)).astype(np.float32)
+        dbg = hp.backward_sgd(hb_b, torch.from_numpy(g_np).to(dev), lr, debug=True)
+        hp.sync()
+        Wo = [x.copy() for x in W0]
+        uniq, runlen, mag = O.embbag_bwd_sgd(Wo, S_, [s0, s1b], [None, None], g_np, lr, want_mag=True)
+        for z in range(2):
+            assert np.array_equal(dbg[0][z].cpu().numpy(), uniq[z]), f"distinct slots of table {z} differ (fused={fused})"
+            assert np.array_equal(dbg[1][z].cpu().numpy(), runlen[z])
+            got = hp.hotW[z].cpu().numpy()
+            touched = np.zeros(n_hot[z], dtype=bool)
+            touched[uniq[z]] = True
+            assert got[~touched].tobytes() == W0[z][~touched].tobytes()
+            T.assert_close_sum(got[uniq[z]], Wo[z][uniq[z]], mag[z], f"updated rows of table {z} (fused={fused})")
