@@ -260,6 +260,23 @@ int32_t fae_embbag_bwd_sgd(fae_ctx *ctx, const fae_tables *hot_tables, float *co
                            const fae_batch *hot_batch, const float *gout, int64_t gout_row_stride,
                            float lr, const fae_bwd_debug *dbg, void *ws, size_t ws_bytes);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): fae_embbag_bwd_sgd with the workspace inside the
+ * library instead of the caller's.  The workspace is one array of FAE_BWD_STATIC_WS_BYTES per
+ * device, part of the library's code object (every device the library runs on holds it until the
+ * process ends); the call allocates and frees nothing.  Same arguments, results and error
+ * behaviour as fae_embbag_bwd_sgd without the optional outputs; a batch whose
+ * fae_bwd_workspace_bytes() exceeds FAE_BWD_STATIC_WS_BYTES is rejected with FAE_ENOSPC before
+ * anything is launched (the need is about 32 bytes per lookup at dim 64, so about 1 M lookups
+ * fit; fae_bwd_static_workspace_bytes() returns the limit).  Every call on a device uses that device's one array, which keeps the last call's
+ * contents (the call clears what must start at zero): calls that overlap on one device, from
+ * several contexts or streams, race; calls on one stream are ordered.  Asynchronous. */
+#define FAE_BWD_STATIC_WS_BYTES (32u << 20)
+size_t fae_bwd_static_workspace_bytes(void);
+int32_t fae_embbag_bwd_sgd_static(fae_ctx *ctx, const fae_tables *hot_tables, float *const *h_hotW,
+                                  const fae_batch *hot_batch, const float *gout, int64_t gout_row_stride,
+                                  float lr);
+
 /* ---- pooling and optimizer variants ----------------------------------------------
  * The paper names the pooled embedding lookup and the optimizer step (Sec. 2.2) without
  * fixing either; fae_embbag_fwd / fae_embbag_bwd_sgd are sum pooling and plain SGD.  These

@@ -29,7 +29,7 @@ EXPORTS = [
     "fae_build_workspace_bytes", "fae_build_hot_tables", "fae_partition_workspace_bytes",
     "fae_partition_batch", "fae_embbag_fwd", "fae_bwd_workspace_bytes", "fae_embbag_bwd_presort",
     "fae_embbag_fwd_presort",
-    "fae_embbag_bwd_sgd",
+    "fae_embbag_bwd_sgd", "fae_bwd_static_workspace_bytes", "fae_embbag_bwd_sgd_static",
     "fae_sync_hot_rows", "fae_estimate_workspace_bytes", "fae_estimate_hot", "fae_choose_cutoff_sampled",
     "fae_t_quantile", "fae_sched_init", "fae_sched_report", "fae_sched_segment",
     "fae_embbag_fwd_opts", "fae_embbag_bwd_opts",
@@ -93,7 +93,8 @@ def load():
     lib.fae_last_error.argtypes = [C.c_void_p]
     lib.fae_version.restype = C.c_char_p
     for name in ("fae_choose_cutoff_workspace_bytes", "fae_build_workspace_bytes",
-                 "fae_partition_workspace_bytes", "fae_bwd_workspace_bytes", "fae_estimate_workspace_bytes"):
+                 "fae_partition_workspace_bytes", "fae_bwd_workspace_bytes", "fae_estimate_workspace_bytes",
+                 "fae_bwd_static_workspace_bytes"):
         getattr(lib, name).restype = C.c_size_t
     lib.fae_destroy.restype = None
     lib.fae_kernel_name.restype = C.c_char_p
@@ -371,6 +372,18 @@ def fae_embbag_bwd_sgd(ctx: Context, hot_tables: Tables, hotW: List[torch.Tensor
     ctx.check(load().fae_embbag_bwd_sgd(ctx._h, C.byref(t), _ptrs(hotW, torch.float32), C.byref(b),
                                         _ptr(gout, torch.float32), C.c_int64(gout_row_stride), C.c_float(lr),
                                         dbg, _ptr(ws, torch.uint8), C.c_size_t(ws.numel())))
+
+
+def fae_bwd_static_workspace_bytes() -> int:
+    return int(load().fae_bwd_static_workspace_bytes())
+
+
+def fae_embbag_bwd_sgd_static(ctx: Context, hot_tables: Tables, hotW: List[torch.Tensor], hot_batch: Batch,
+                              gout: torch.Tensor, gout_row_stride: int, lr: float):
+    """fae_embbag_bwd_sgd on the library's built-in workspace (nothing is allocated)."""
+    t, b = hot_tables.c(), hot_batch.c()
+    ctx.check(load().fae_embbag_bwd_sgd_static(ctx._h, C.byref(t), _ptrs(hotW, torch.float32), C.byref(b),
+                                               _ptr(gout, torch.float32), C.c_int64(gout_row_stride), C.c_float(lr)))
 
 
 def _step_opts(pooling: int, optimizer: int, lr: float, eps: float, state: Optional[List[torch.Tensor]]):

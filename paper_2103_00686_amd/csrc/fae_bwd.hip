@@ -25,6 +25,8 @@
 // fae_bwd_sort.hip, steps 3 + 4 in fae_bwd_reduce.hip, what they share in fae_bwd.h.
 #include "fae_bwd.h"
 
+#include <mutex>
+
 // ---------------------------------------------------------------------------------
 // plan and workspace
 // ---------------------------------------------------------------------------------
@@ -301,4 +303,69 @@ static int32_t bwd_impl(fae_ctx *ctx, const fae_tables *hot_tables, float *const
             return rc;
     }
     return FAE_OK;
+}
+
+// ---------------------------------------------------------------------------------
+// The backward for callers that cannot allocate: the workspace lives inside the library.
+// ---------------------------------------------------------------------------------
+// One array per device (every device that loads the library's code object holds its own copy at
+// its own address until the process ends).  In host code the array's name only stands for the
+// symbol: the device address comes from hipGetSymbolAddress, once per device with that device
+// current, and is what every launch and fill is given.
+static __device__ __align__(256) unsigned char fae_bwd_scratch[FAE_BWD_STATIC_WS_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxDevices] = {nullptr};
+} // namespace
+
+// Device address of this device's copy of the array (resolved at most once per device).  The
+// caller has made `device` current.
+int32_t fae_bwd_scratch_resolve(fae_ctx *ctx, int device, void **out)
+{
+    *out = nullptr;
+    if (device < 0 || device >= kMaxDevices)
+        return fae_fail(ctx, FAE_EINVAL, "built-in workspace: device %d outside [0,%d)", device, kMaxDevices);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[device]) {
+        void *ptr = nullptr;
+        FAE_HIP(ctx, hipGetSymbolAddress((void **)&ptr, HIP_SYMBOL(fae_bwd_scratch)));
+        if (!ptr)
+            return fae_fail(ctx, FAE_EHIP, "built-in workspace: no device address for device %d", device);
+        g_scratch_ptr[device] = ptr;
+    }
+    *out = g_scratch_ptr[device];
+    return FAE_OK;
+}
+
+extern "C" size_t fae_bwd_static_workspace_bytes(void) { return (size_t)FAE_BWD_STATIC_WS_BYTES; }
+
+extern "C" int32_t fae_embbag_bwd_sgd_static(fae_ctx *ctx, const fae_tables *hot_tables, float *const *h_hotW,
+                                             const fae_batch *hot_batch, const float *gout, int64_t gout_row_stride,
+                                             float lr)
+{
+    if (!ctx)
+        return FAE_EINVAL;
+    int32_t rc = fae_check_tables(ctx, hot_tables, "fae_embbag_bwd_sgd_static");
+    if (rc != FAE_OK)
+        return rc;
+    rc = fae_check_batch(ctx, hot_tables, hot_batch, "fae_embbag_bwd_sgd_static");
+    if (rc != FAE_OK)
+        return rc;
+    const size_t need = fae_bwd_workspace_bytes(hot_tables, hot_batch->n_samples, hot_batch->h_n_lookups);
+    if (need == 0 || need > (size_t)FAE_BWD_STATIC_WS_BYTES)
+        return fae_fail(ctx, FAE_ENOSPC,
+                        "fae_embbag_bwd_sgd_static: this batch needs %zu bytes of workspace, the built-in one has %zu; "
+                        "use fae_embbag_bwd_sgd with a workspace of the caller's",
+                        need, (size_t)FAE_BWD_STATIC_WS_BYTES);
+    if (!ctx->bwd_scratch) // resolved by fae_create; a context made before that is possible resolves it here
+    {
+        FAE_HIP(ctx, hipSetDevice(ctx->device));
+        rc = fae_bwd_scratch_resolve(ctx, ctx->device, &ctx->bwd_scratch);
+        if (rc != FAE_OK)
+            return rc;
+    }
+    return fae_embbag_bwd_sgd(ctx, hot_tables, h_hotW, hot_batch, gout, gout_row_stride, lr, nullptr,
+                              ctx->bwd_scratch, (size_t)FAE_BWD_STATIC_WS_BYTES);
 }

@@ -75,6 +75,13 @@ extern "C" int32_t fae_create(fae_ctx **out, int32_t device, void *hip_stream)
         return FAE_EHIP;
     }
     memset(ctx->h_block, 0, FAE_BLK_WORDS * sizeof(uint32_t));
+    // the built-in backward workspace of this device (the device is current here)
+    if (fae_bwd_scratch_resolve(ctx, device, &ctx->bwd_scratch) != FAE_OK) {
+        (void)hipFree(ctx->d_block);
+        (void)hipHostFree(ctx->h_block);
+        delete ctx;
+        return FAE_EHIP;
+    }
     if (!fae_make_side_streams(ctx) || !fae_make_join_events(ctx)) {
         (void)hipFree(ctx->d_block);
         (void)hipHostFree(ctx->h_block);

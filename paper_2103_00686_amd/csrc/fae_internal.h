@@ -49,6 +49,9 @@ struct fae_ctx {
     int64_t opt_probe_nt = -1;         // non-temporal accesses: 0, 1
     int64_t opt_probe_wgs_per_cu = 0;  // 0: one workgroup per chunk; n: n workgroups per compute unit striding over the chunks
     char err[512] = {0};
+    // device address of this device's copy of the library's built-in backward workspace
+    // (fae_embbag_bwd_sgd_static); resolved by fae_create
+    void *bwd_scratch = nullptr;
     // side stream for work that may overlap the main stream (backward presort)
     // two of them, taken in turn: the sorts of consecutive batches may overlap each other
     static constexpr int N_AUX = 2;
@@ -137,6 +140,8 @@ struct fae_ktimer {
 };
 
 int32_t fae_fail(fae_ctx *ctx, int32_t code, const char *fmt, ...);
+// fae_bwd.hip: device address of the built-in backward workspace on `device` (which is current)
+int32_t fae_bwd_scratch_resolve(fae_ctx *ctx, int device, void **out);
 // copy n words of the device block (from word `first`) to the pinned block and wait
 int32_t fae_readback(fae_ctx *ctx, int first, int n);
 // wait for the stream, fetch + clear the sticky status; maps it to an error code
