@@ -239,12 +239,26 @@ __device__ __forceinline__ void bwd_finish_borders(const BwdArgs &a, const SpanI
         *wp = bwd_vec<V>::sgd(wv, acc, step);
 }
 
-template <typename V, int LPR> __global__ __launch_bounds__(256) void bwd_reduce_kernel(BwdArgs a)
+// One batch of the reduce kernel's main loop: UN steps of G gradient rows each, and whatever
+// else those steps read (the weight row of a run that ends there, its Adagrad accumulator).
+template <typename V, int UN, bool VAR> struct BwdBatch {
+    int kk[UN], dd[UN];
+    V vv[UN], ww[UN];
+    float inv[VAR ? UN : 1], sw[VAR ? UN : 1];
+};
+
+// UN = steps per batch; the loads of a batch are issued before the batch in front of it is summed
+// (two batches alternate), so a wave always has rows on their way while it works.  VAR = mean
+// pooling or Adagrad may be asked for (the plain kernel carries neither their registers nor
+// their branches).
+template <typename V, int LPR, int UNMAX, bool VAR> __global__ __launch_bounds__(256) void bwd_reduce_kernel(BwdArgs a)
 {
     constexpr int G = FAE_WAVE / LPR;              // lane groups = gradient rows per step
     constexpr int VW = sizeof(V) / sizeof(float);
     constexpr int STEPS = FAE_WAVE / G;            // steps per tile of 64 lookups
-    constexpr int UN = STEPS < 4 ? STEPS : 4;      // steps whose loads are issued together
+    constexpr int UN = STEPS < UNMAX ? STEPS : UNMAX; // steps whose loads are issued together
+    constexpr int NBATCH = STEPS / UN;
+    typedef BwdBatch<V, UN, VAR> Batch;
     // the same for every lane of a wave: said so, the span's bookkeeping runs on the scalar unit
     const int sid = blockIdx.x * a.wg_waves + __builtin_amdgcn_readfirstlane(threadIdx.x / FAE_WAVE);
     // the table is looked up before the range check: kernel arguments only, so these loads leave
@@ -252,17 +266,29 @@ template <typename V, int LPR> __global__ __launch_bounds__(256) void bwd_reduce
     const int z_of_span = fae_find_table(a.blk_start, a.n_tables, sid);
     if (sid >= a.n_spans)
         return;
+    const int lane = fae_lane(), g = lane / LPR, l = lane % LPR;
+    // The span's place follows from the kernel arguments alone, so the pairs of its first 64
+    // lookups are asked for in the same round as the status word and the span's border keys.
+    int knext_tile, snext_tile;
+    {
+        const int seg0 = a.seg_start[z_of_span], seg1 = a.seg_start[z_of_span + 1];
+        const int pos0 = seg0 + (sid - a.blk_start[z_of_span]) * a.span;
+        const int pos1 = pos0 + a.span < seg1 ? pos0 + a.span : seg1;
+        const int p = pos0 + lane;
+        knext_tile = p < pos1 ? a.keys_in[p] : KEY_NONE;
+        snext_tile = p < pos1 ? a.vals_in[p] : 0;
+    }
     // a bounded wait of the sort stage gave up: the pairs are not what they should be
     const uint32_t status = __hip_atomic_load(a.status + FAE_BLK_STATUS, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     const SpanInfo sp = bwd_span_info(a, sid, z_of_span);
     if (status & FAE_STATUS_EINTERNAL)
         return;
-    const int lane = fae_lane(), g = lane / LPR, l = lane % LPR;
     const int ncols = a.dim / VW;
     const int n_hot = a.n_hot[sp.z];
     V *W = (V *)a.W[sp.z];
     const float *gbase = a.gout + (int64_t)sp.z * a.dim;
     V *part = (V *)(a.partial + (int64_t)sid * 2 * a.dim);
+    const bool mean = VAR && a.mean, adagrad = VAR && a.adagrad;
 
     for (int c0 = 0; c0 < ncols; c0 += LPR) {
         const int c = c0 + l;
@@ -272,16 +298,26 @@ template <typename V, int LPR> __global__ __launch_bounds__(256) void bwd_reduce
         V cv = bwd_vec<V>::zero();
         int klast = KEY_NONE; // last key of the previous tile (none at the span's start)
         int dist_in = 0;      // position inside its run of a lookup that continues the previous tile's last run
+        if (c0 > 0) { // rows wider than one pass over the lanes: the first tile's pairs again
+            const int p = sp.pos0 + lane;
+            knext_tile = p < sp.pos1 ? a.keys_in[p] : KEY_NONE;
+            snext_tile = p < sp.pos1 ? a.vals_in[p] : 0;
+        }
         for (int t0 = sp.pos0; t0 < sp.pos1; t0 += FAE_WAVE) {
             const int p = t0 + lane;
-            const int kreg = p < sp.pos1 ? a.keys_in[p] : KEY_NONE;
-            const int sreg = p < sp.pos1 ? a.vals_in[p] : 0;
+            const int kreg = knext_tile;
+            const int sreg = snext_tile;
             // key that follows each lookup; the span's last lookup always closes its run here
             int kafter = __shfl_down(kreg, 1, FAE_WAVE);
             if (lane == FAE_WAVE - 1)
                 kafter = t0 + FAE_WAVE < sp.pos1 ? a.keys_in[t0 + FAE_WAVE] : KEY_NONE;
             if (p == sp.pos1 - 1)
                 kafter = KEY_NONE;
+            { // the pairs of the next tile: asked for now, used after this tile's rows
+                const int pn = p + FAE_WAVE;
+                knext_tile = pn < sp.pos1 ? a.keys_in[pn] : KEY_NONE;
+                snext_tile = pn < sp.pos1 ? a.vals_in[pn] : 0;
+            }
             // where the finished run of lookup p goes: 0 nowhere (not the last of its run, or an
             // invalid slot), 1 SGD on its row, 2 / 3 the span's head / tail scratch row
             int dreg = 0;
@@ -299,38 +335,39 @@ template <typename V, int LPR> __global__ __launch_bounds__(256) void bwd_reduce
             dist = dist < 255 ? dist : 255;
             dreg |= dist << 2;
             float ireg = 1.0f; // mean pooling: 1 / (lookups in the lookup's bag)
-            if (a.mean && a.offsets[sp.z] && p < sp.pos1) {
+            if (mean && a.offsets[sp.z] && p < sp.pos1) {
                 const int32_t *off = a.offsets[sp.z];
                 const int len = off[sreg + 1] - off[sreg];
                 ireg = 1.0f / (float)(len > 0 ? len : 1);
             }
             klast = __builtin_amdgcn_readlane(kreg, FAE_WAVE - 1);
             dist_in = __builtin_amdgcn_readlane(dist, FAE_WAVE - 1) + 1;
-            for (int i0 = 0; i0 < STEPS; i0 += UN) {
-                if (t0 + i0 * G >= sp.pos1)
-                    break;
-                int kk[UN], dd[UN];
-                V vv[UN], ww[UN];
-                float inv[UN], sw[UN];
-#pragma unroll
-                for (int u = 0; u < UN; ++u) { // every load of the batch is issued before the first use
-                    const int e = (i0 + u) * G + g;
-                    kk[u] = __shfl(kreg, e, FAE_WAVE);
-                    dd[u] = __shfl(dreg, e, FAE_WAVE);
-                    const int s = __shfl(sreg, e, FAE_WAVE);
-                    inv[u] = a.mean ? __shfl(ireg, e, FAE_WAVE) : 1.0f;
-                    vv[u] = (active && kk[u] != KEY_NONE) ? ((const V *)(gbase + (int64_t)s * a.gout_stride))[c]
-                                                         : bwd_vec<V>::zero();
-                    ww[u] = (active && (dd[u] & 3) == 1) ? W[(int64_t)kk[u] * ncols + c] : bwd_vec<V>::zero();
-                    sw[u] = (a.adagrad && (dd[u] & 3) == 1) ? a.opt_state[sp.z][kk[u]] : 0.f;
-                }
+
+            // every load of a batch is issued before the first use of any of them
+            auto issue = [&](Batch &b, int i0) {
 #pragma unroll
                 for (int u = 0; u < UN; ++u) {
-                    const int kg = kk[u];
-                    const int dest = dd[u] & 3, dist_u = dd[u] >> 2;
-                    V vg = vv[u];
-                    if (a.mean)
-                        bwd_vec<V>::scale(vg, inv[u]);
+                    const int e = (i0 + u) * G + g;
+                    b.kk[u] = __shfl(kreg, e, FAE_WAVE);
+                    b.dd[u] = __shfl(dreg, e, FAE_WAVE);
+                    const int s = __shfl(sreg, e, FAE_WAVE);
+                    if (VAR)
+                        b.inv[u] = mean ? __shfl(ireg, e, FAE_WAVE) : 1.0f;
+                    b.vv[u] = (active && b.kk[u] != KEY_NONE) ? ((const V *)(gbase + (int64_t)s * a.gout_stride))[c]
+                                                             : bwd_vec<V>::zero();
+                    b.ww[u] = (active && (b.dd[u] & 3) == 1) ? W[(int64_t)b.kk[u] * ncols + c] : bwd_vec<V>::zero();
+                    if (VAR)
+                        b.sw[u] = (adagrad && (b.dd[u] & 3) == 1) ? a.opt_state[sp.z][b.kk[u]] : 0.f;
+                }
+            };
+            auto sum = [&](Batch &b) {
+#pragma unroll
+                for (int u = 0; u < UN; ++u) {
+                    const int kg = b.kk[u];
+                    const int dest = b.dd[u] & 3, dist_u = b.dd[u] >> 2;
+                    V vg = b.vv[u];
+                    if (mean)
+                        bwd_vec<V>::scale(vg, b.inv[u]);
                     // Inclusive segmented scan over the lane groups, the open run of the previous step
                     // standing in front of group 0: a rotation by d groups brings group g - d to
                     // group g, and the carried sum (held by the last group) to group d - 1.
@@ -344,19 +381,19 @@ template <typename V, int LPR> __global__ __launch_bounds__(256) void bwd_reduce
                     if (g == G - 1 && dist_u >= G)
                         bwd_vec<V>::add(vg, cv); // the last group reaches back past group 0
                     float step = a.lr;
-                    if (a.adagrad) { // one accumulator per row: grows by the row's mean squared gradient
+                    if (adagrad) { // one accumulator per row: grows by the row's mean squared gradient
                         float q = bwd_vec<V>::sumsq(vg);
 #pragma unroll
                         for (int m = 1; m < LPR; m <<= 1)
                             q += __shfl_xor(q, m, FAE_WAVE);
-                        const float acc = sw[u] + q / (float)a.dim;
+                        const float acc = b.sw[u] + q / (float)a.dim;
                         step = a.lr / (sqrtf(acc) + a.eps);
                         if (dest == 1 && l == 0)
                             a.opt_state[sp.z][kg] = acc;
                     }
                     if (active) {
                         if (dest == 1)
-                            W[(int64_t)kg * ncols + c] = bwd_vec<V>::sgd(ww[u], vg, step);
+                            W[(int64_t)kg * ncols + c] = bwd_vec<V>::sgd(b.ww[u], vg, step);
                         else if (dest == 2) {
                             if (a.fused_fixup)
                                 bwd_store_shared(&part[c], vg);
@@ -370,6 +407,23 @@ template <typename V, int LPR> __global__ __launch_bounds__(256) void bwd_reduce
                         }
                     }
                     cv = vg; // used from the last group only
+                }
+            };
+            // batches past the span's end hold nothing: they are neither asked for nor summed
+            const int n_batch = (sp.pos1 - t0 >= FAE_WAVE) ? NBATCH : ((sp.pos1 - t0) + UN * G - 1) / (UN * G);
+            Batch b0, b1;
+            issue(b0, 0);
+#pragma unroll
+            for (int ib = 0; ib < NBATCH; ib += 2) {
+                if (ib >= n_batch)
+                    break;
+                if (ib + 1 < NBATCH && ib + 1 < n_batch)
+                    issue(b1, (ib + 1) * UN);
+                sum(b0);
+                if (ib + 1 < NBATCH && ib + 1 < n_batch) {
+                    if (ib + 2 < NBATCH && ib + 2 < n_batch)
+                        issue(b0, (ib + 2) * UN);
+                    sum(b1);
                 }
             }
         }
@@ -728,7 +782,18 @@ template <typename V, int LPR> void launch_reduce(fae_ctx *ctx, const BwdArgs &a
         if (a.form == 1)
             launch_walk<V, LPR>(ctx, a, grid, block);
         else
-            hipLaunchKernelGGL((bwd_reduce_kernel<V, LPR>), grid, block, 0, ctx->stream, a);
+        {
+            // steps per batch: two where a step moves whole rows with few lanes to spare (long rows),
+            // four otherwise; reduce_unroll 2 / 4 forces one
+            const bool var = a.mean || a.adagrad;
+            const int un = ctx->opt_unroll == 2 ? 2 : (ctx->opt_unroll == 4 ? 4 : 2);
+            if (var)
+                hipLaunchKernelGGL((bwd_reduce_kernel<V, LPR, 2, true>), grid, block, 0, ctx->stream, a);
+            else if (un == 2)
+                hipLaunchKernelGGL((bwd_reduce_kernel<V, LPR, 2, false>), grid, block, 0, ctx->stream, a);
+            else
+                hipLaunchKernelGGL((bwd_reduce_kernel<V, LPR, 4, false>), grid, block, 0, ctx->stream, a);
+        }
     }
     if (a.fused_fixup)
         return;

@@ -252,7 +252,7 @@ extern "C" int32_t fae_set_option(fae_ctx *ctx, const char *name, int64_t value)
         ctx->opt_reduce = value;
     else if (!strcmp(name, "reduce_wg_waves") && (value == 0 || value == 1 || value == 2 || value == 4))
         ctx->opt_wg_waves = value;
-    else if (!strcmp(name, "reduce_unroll") && (value == 0 || value == 4 || value == 8))
+    else if (!strcmp(name, "reduce_unroll") && (value == 0 || value == 2 || value == 4 || value == 8))
         ctx->opt_unroll = value;
     else if (!strcmp(name, "handoff_fences") && value >= 0 && value <= 1)
         ctx->opt_handoff = value;
