@@ -180,8 +180,9 @@ extern "C" int32_t fae_profile(fae_ctx *ctx, const fae_tables *tables, const fae
 // a2  hot cutoff: how many rows have count >= H, for a window of H values   (Eq. 2)
 // =================================================================================
 #define CW_BINS 2048
-#define CW_TILE 4096
+#define CW_TILE 8192 // rows per workgroup: 32 per thread, eight 16-byte loads
 #define CW_STRIDE (CW_BINS + 2) // per table: bins, rows above the window, max count
+#define CW_LOCAL 4 // the lowest bins of the window are counted in registers
 
 struct CwArgs {
     const uint32_t *cnt[FAE_MAX_TABLES];
@@ -189,11 +190,24 @@ struct CwArgs {
     uint32_t lo[FAE_MAX_TABLES];
     int32_t blk_start[FAE_MAX_TABLES + 1];
     int32_t n_tables;
+    int32_t tiles_per_wg; // consecutive tiles of CW_TILE rows a workgroup counts before it merges
     uint32_t *hist; // [n_tables][CW_STRIDE], zeroed by the caller
 };
 
+// sum of v over the lanes of a wave (every lane gets it)
+__device__ __forceinline__ uint32_t cw_wave_sum(uint32_t v)
+{
+#pragma unroll
+    for (int m = 1; m < FAE_WAVE; m <<= 1)
+        v += __shfl_xor(v, m, FAE_WAVE);
+    return v;
+}
+
 // hist[z][b] = #rows with count == lo_z + b (b < CW_BINS); hist[z][CW_BINS] = #rows
 // with count >= lo_z + CW_BINS; hist[z][CW_BINS+1] = max count.
+// Under a skewed access law almost every row sits in the first bins of the window (never or once
+// accessed), so one LDS counter per bin would have a whole wave hammering the same word: the
+// CW_LOCAL lowest bins are counted in registers and added up per wave; the rest go to LDS.
 __global__ __launch_bounds__(256) void count_window_kernel(CwArgs a)
 {
     __shared__ uint32_t bins[CW_BINS + 2];
@@ -205,23 +219,56 @@ __global__ __launch_bounds__(256) void count_window_kernel(CwArgs a)
     for (int i = threadIdx.x; i < CW_BINS + 2; i += 256)
         bins[i] = 0u;
     __syncthreads();
-    const int64_t beg = (int64_t)bl * CW_TILE;
     uint32_t above = 0, mx = 0;
-    for (int k = 0; k < CW_TILE / 256; ++k) {
-        int64_t r = beg + k * 256 + threadIdx.x;
-        if (r < R) {
-            uint32_t v = cnt[r];
-            mx = v > mx ? v : mx;
-            if (v >= lo) {
-                uint32_t b = v - lo;
-                if (b >= CW_BINS)
-                    above += 1;
-                else
-                    atomicAdd(&bins[b], 1u);
+    uint32_t local[CW_LOCAL] = {0, 0, 0, 0};
+    auto count = [&](uint32_t v) {
+        mx = v > mx ? v : mx;
+        if (v >= lo) {
+            const uint32_t b = v - lo;
+#pragma unroll
+            for (int q = 0; q < CW_LOCAL; ++q)
+                local[q] += b == (uint32_t)q ? 1u : 0u;
+            if (b >= CW_BINS)
+                above += 1;
+            else if (b >= CW_LOCAL)
+                atomicAdd(&bins[b], 1u);
+        }
+    };
+    constexpr int VEC = CW_TILE / 256 / 4; // 16-byte loads per thread
+    // several tiles per workgroup: the merge into the table's bins (the same few words for every
+    // workgroup of a table) is paid once per workgroup, not once per tile
+    for (int t = 0; t < a.tiles_per_wg; ++t) {
+        const int64_t beg = ((int64_t)bl * a.tiles_per_wg + t) * CW_TILE;
+        if (beg >= R)
+            break;
+        if (beg + CW_TILE <= R && (((uintptr_t)(cnt + beg)) & 15) == 0) {
+            uint4 v[VEC];
+#pragma unroll
+            for (int k = 0; k < VEC; ++k) // every load is issued before the first is counted
+                v[k] = ((const uint4 *)(cnt + beg))[k * 256 + threadIdx.x];
+#pragma unroll
+            for (int k = 0; k < VEC; ++k) {
+                count(v[k].x);
+                count(v[k].y);
+                count(v[k].z);
+                count(v[k].w);
+            }
+        } else {
+            for (int k = 0; k < CW_TILE / 256; ++k) {
+                const int64_t r = beg + k * 256 + threadIdx.x;
+                if (r < R)
+                    count(cnt[r]);
             }
         }
     }
-    if (above)
+#pragma unroll
+    for (int q = 0; q < CW_LOCAL; ++q) {
+        const uint32_t c = cw_wave_sum(local[q]);
+        if (fae_lane() == 0 && c)
+            atomicAdd(&bins[q], c);
+    }
+    above = cw_wave_sum(above);
+    if (fae_lane() == 0 && above)
         atomicAdd(&bins[CW_BINS], above);
     if (mx)
         atomicMax(&bins[CW_BINS + 1], mx);
@@ -257,14 +304,21 @@ struct Window {
         const int nt = t->n_tables;
         CwArgs a;
         memset(&a, 0, sizeof(a));
-        int64_t blocks = 0;
+        int64_t blocks = 0, tiles = 0;
+        for (int z = 0; z < nt; ++z)
+            tiles += (t->h_rows[z] + CW_TILE - 1) / CW_TILE;
+        // about eight workgroups per compute unit, each counting a run of consecutive tiles
+        int64_t per = (tiles + 8LL * ctx->n_cu - 1) / (8LL * ctx->n_cu);
+        if (per < 1)
+            per = 1;
+        a.tiles_per_wg = (int32_t)per;
         for (int z = 0; z < nt; ++z) {
             lo[z] = new_lo[z];
             a.cnt[z] = h_counts[z];
             a.n_rows[z] = (int32_t)t->h_rows[z];
             a.lo[z] = lo[z];
             a.blk_start[z] = (int32_t)blocks;
-            blocks += (t->h_rows[z] + CW_TILE - 1) / CW_TILE;
+            blocks += ((t->h_rows[z] + CW_TILE - 1) / CW_TILE + per - 1) / per;
         }
         a.blk_start[nt] = (int32_t)blocks;
         a.n_tables = nt;
@@ -516,20 +570,27 @@ __global__ __launch_bounds__(256) void build_scatter_kernel(BuildArgs a)
     int32_t *remap = a.remap[z];
     int32_t *hot_ids = a.hot_ids[z];
     bool over = false;
+    int32_t rm[8];
 #pragma unroll
     for (int k = 0; k < 8; ++k) {
-        if (r0 + k < R) {
-            if (v[k] >= H) {
-                remap[r0 + k] = slot;
-                if (slot < cap)
-                    hot_ids[slot] = (int32_t)(r0 + k);
-                else
-                    over = true;
-                ++slot;
-            } else {
-                remap[r0 + k] = -1;
-            }
+        rm[k] = -1;
+        if (r0 + k < R && v[k] >= H) {
+            rm[k] = slot;
+            if (slot < cap)
+                hot_ids[slot] = (int32_t)(r0 + k);
+            else
+                over = true;
+            ++slot;
         }
+    }
+    if (r0 + 8 <= R && (((uintptr_t)(remap + r0)) & 15) == 0) { // the eight entries as two 16-byte stores
+        *(int4 *)(remap + r0) = make_int4(rm[0], rm[1], rm[2], rm[3]);
+        *(int4 *)(remap + r0 + 4) = make_int4(rm[4], rm[5], rm[6], rm[7]);
+    } else {
+#pragma unroll
+        for (int k = 0; k < 8; ++k)
+            if (r0 + k < R)
+                remap[r0 + k] = rm[k];
     }
     if (over)
         fae_flag(a.status, FAE_STATUS_ENOSPC);
