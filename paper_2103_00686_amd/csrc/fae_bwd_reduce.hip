@@ -768,9 +768,9 @@ template <typename V, int LPR> void launch_walk(fae_ctx *ctx, const BwdArgs &a, 
 {
     if constexpr (sizeof(V) == sizeof(float4) && LPR >= 4) {
         if (ctx->opt_unroll != 4 && a.span / (FAE_WAVE / LPR) >= 8)
-            hipLaunchKernelGGL((bwd_reduce_walk_kernel<LPR, 8>), grid, block, 0, ctx->stream, a);
+            FAE_LAUNCH(ctx, (bwd_reduce_walk_kernel<LPR, 8>), grid, block, 0, ctx->stream, a);
         else
-            hipLaunchKernelGGL((bwd_reduce_walk_kernel<LPR, 4>), grid, block, 0, ctx->stream, a);
+            FAE_LAUNCH(ctx, (bwd_reduce_walk_kernel<LPR, 4>), grid, block, 0, ctx->stream, a);
     }
 }
 
@@ -788,17 +788,17 @@ template <typename V, int LPR> void launch_reduce(fae_ctx *ctx, const BwdArgs &a
             const bool var = a.mean || a.adagrad;
             const int un = ctx->opt_unroll == 2 ? 2 : (ctx->opt_unroll == 4 ? 4 : 2);
             if (var)
-                hipLaunchKernelGGL((bwd_reduce_kernel<V, LPR, 2, true>), grid, block, 0, ctx->stream, a);
+                FAE_LAUNCH(ctx, (bwd_reduce_kernel<V, LPR, 2, true>), grid, block, 0, ctx->stream, a);
             else if (un == 2)
-                hipLaunchKernelGGL((bwd_reduce_kernel<V, LPR, 2, false>), grid, block, 0, ctx->stream, a);
+                FAE_LAUNCH(ctx, (bwd_reduce_kernel<V, LPR, 2, false>), grid, block, 0, ctx->stream, a);
             else
-                hipLaunchKernelGGL((bwd_reduce_kernel<V, LPR, 4, false>), grid, block, 0, ctx->stream, a);
+                FAE_LAUNCH(ctx, (bwd_reduce_kernel<V, LPR, 4, false>), grid, block, 0, ctx->stream, a);
         }
     }
     if (a.fused_fixup)
         return;
     fae_ktimer kt(ctx, FAE_K_BWD_FIXUP);
-    hipLaunchKernelGGL((bwd_fixup_kernel<V, LPR>), dim3((a.n_spans + 3) / 4), dim3(256), 0, ctx->stream, a);
+    FAE_LAUNCH(ctx, (bwd_fixup_kernel<V, LPR>), dim3((a.n_spans + 3) / 4), dim3(256), 0, ctx->stream, a);
 }
 
 #define BWD_LPR_SWITCH(V, lpr, CALL)      \
@@ -827,17 +827,17 @@ void bwd_launch_reduce(fae_ctx *ctx, const BwdArgs &a, bool vec, int lpr)
 int32_t bwd_launch_debug(fae_ctx *ctx, BwdArgs &a)
 {
     const int64_t N = a.seg_start[a.n_tables];
-    hipLaunchKernelGGL(dbg_count_kernel, dim3((unsigned)a.dbg_tiles), dim3(256), 0, ctx->stream, a);
+    FAE_LAUNCH(ctx, dbg_count_kernel, dim3((unsigned)a.dbg_tiles), dim3(256), 0, ctx->stream, a);
     FAE_LAUNCH_CHECK(ctx);
     int32_t rc = fae_scan_i32(ctx, a.dbg_tile_sums, a.dbg_tiles);
     if (rc != FAE_OK)
         return rc;
-    hipLaunchKernelGGL(dbg_emit_kernel, dim3((unsigned)a.dbg_tiles), dim3(256), 0, ctx->stream, a);
+    FAE_LAUNCH(ctx, dbg_emit_kernel, dim3((unsigned)a.dbg_tiles), dim3(256), 0, ctx->stream, a);
     FAE_LAUNCH_CHECK(ctx);
     int rl_blocks = (int)((N + 255) / 256);
     if (rl_blocks > 4096)
         rl_blocks = 4096;
-    hipLaunchKernelGGL(dbg_runlen_kernel, dim3(rl_blocks), dim3(256), 0, ctx->stream, a);
+    FAE_LAUNCH(ctx, dbg_runlen_kernel, dim3(rl_blocks), dim3(256), 0, ctx->stream, a);
     FAE_LAUNCH_CHECK(ctx);
     return FAE_OK;
 }

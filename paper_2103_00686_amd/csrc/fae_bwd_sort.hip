@@ -576,7 +576,7 @@ int32_t bwd_sort_stage(fae_ctx *ctx, hipStream_t st, const fae_tables *hot_table
         a.vals_in = w.vals[0];
         if (blocks > 0) {
             fae_ktimer kt(ctx, FAE_K_BWD_KEYS, st);
-            hipLaunchKernelGGL(bwd_keys_kernel, dim3((unsigned)blocks), dim3(256), 0, st, a);
+            FAE_LAUNCH(ctx, bwd_keys_kernel, dim3((unsigned)blocks), dim3(256), 0, st, a);
             FAE_LAUNCH_CHECK(ctx);
         }
     }
@@ -593,26 +593,26 @@ int32_t bwd_sort_stage(fae_ctx *ctx, hipStream_t st, const fae_tables *hot_table
         if (chained) {
             fae_ktimer kt(ctx, FAE_K_SORT_SCATTER, st);
             if (small_tiles)
-                hipLaunchKernelGGL((sort_scatter_kernel<true, SORT_ITEMS_SMALL>), dim3((unsigned)tiles), dim3(SORT_THREADS), 0, st, a);
+                FAE_LAUNCH(ctx, (sort_scatter_kernel<true, SORT_ITEMS_SMALL>), dim3((unsigned)tiles), dim3(SORT_THREADS), 0, st, a);
             else
-                hipLaunchKernelGGL((sort_scatter_kernel<true, SORT_ITEMS>), dim3((unsigned)tiles), dim3(SORT_THREADS), 0, st, a);
+                FAE_LAUNCH(ctx, (sort_scatter_kernel<true, SORT_ITEMS>), dim3((unsigned)tiles), dim3(SORT_THREADS), 0, st, a);
             FAE_LAUNCH_CHECK(ctx);
             cur ^= 1;
             continue;
         }
         {
             fae_ktimer kt(ctx, FAE_K_SORT_HIST, st);
-            hipLaunchKernelGGL(sort_hist_kernel, dim3((unsigned)tiles), dim3(SORT_THREADS), 0, st, a);
+            FAE_LAUNCH(ctx, sort_hist_kernel, dim3((unsigned)tiles), dim3(SORT_THREADS), 0, st, a);
             FAE_LAUNCH_CHECK(ctx);
         }
         {
             fae_ktimer kt(ctx, FAE_K_SORT_COLSCAN, st);
-            hipLaunchKernelGGL(sort_colscan_kernel, dim3((unsigned)((nt * RADIX + 3) / 4)), dim3(256), 0, st, a);
+            FAE_LAUNCH(ctx, sort_colscan_kernel, dim3((unsigned)((nt * RADIX + 3) / 4)), dim3(256), 0, st, a);
             FAE_LAUNCH_CHECK(ctx);
         }
         {
             fae_ktimer kt(ctx, FAE_K_SORT_SCATTER, st);
-            hipLaunchKernelGGL((sort_scatter_kernel<false, SORT_ITEMS>), dim3((unsigned)tiles), dim3(SORT_THREADS), 0, st, a);
+            FAE_LAUNCH(ctx, (sort_scatter_kernel<false, SORT_ITEMS>), dim3((unsigned)tiles), dim3(SORT_THREADS), 0, st, a);
             FAE_LAUNCH_CHECK(ctx);
         }
         cur ^= 1;
@@ -642,7 +642,7 @@ int32_t bwd_sort_stage(fae_ctx *ctx, hipStream_t st, const fae_tables *hot_table
         la.n_flags = a.n_flags;
         la.flag_slice = bwd_flag_slice(a.n_flags, nb);
         fae_ktimer kt(ctx, FAE_K_LDS_SORT, st);
-        hipLaunchKernelGGL(lds_sort_kernel, dim3(nb), dim3(LSORT_THREADS), 0, st, la);
+        FAE_LAUNCH(ctx, lds_sort_kernel, dim3(nb), dim3(LSORT_THREADS), 0, st, la);
         FAE_LAUNCH_CHECK(ctx);
     }
     *cur_out = cur;
@@ -727,7 +727,7 @@ template <typename V, int LPR> __global__ __launch_bounds__(LSORT_THREADS) void 
 
 template <int LPR> static void launch_fwd_sort(fae_ctx *ctx, const FusedArgs &a, int blocks)
 {
-    hipLaunchKernelGGL((fwd_sort_kernel<float4, LPR>), dim3(blocks), dim3(LSORT_THREADS), 0, ctx->stream, a);
+    FAE_LAUNCH(ctx, (fwd_sort_kernel<float4, LPR>), dim3(blocks), dim3(LSORT_THREADS), 0, ctx->stream, a);
 }
 
 extern "C" int32_t fae_embbag_fwd_presort(fae_ctx *ctx, const fae_tables *hot_tables, const float *const *h_hotW,

@@ -88,7 +88,7 @@ extern "C" int32_t fae_create(fae_ctx **out, int32_t device, void *hip_stream)
         delete ctx;
         return FAE_EHIP;
     }
-    hipLaunchKernelGGL(fae_clear_words_kernel, dim3(FAE_BLK_WORDS / 256), dim3(256), 0, ctx->stream,
+    FAE_LAUNCH(ctx, fae_clear_words_kernel, dim3(FAE_BLK_WORDS / 256), dim3(256), 0, ctx->stream,
                        ctx->d_block, FAE_BLK_WORDS);
     if (hipGetLastError() != hipSuccess || hipStreamSynchronize(ctx->stream) != hipSuccess) {
         (void)hipFree(ctx->d_block);
@@ -144,27 +144,28 @@ static hipEvent_t take_event(fae_ctx *c)
     return e;
 }
 
-fae_ktimer::fae_ktimer(fae_ctx *ctx, int id) : fae_ktimer(ctx, id, ctx ? ctx->stream : nullptr) {}
-
-fae_ktimer::fae_ktimer(fae_ctx *ctx, int id, hipStream_t stream) : c(ctx), on(false), st(stream)
+bool fae_timing_begin(fae_ctx *ctx, hipEvent_t *e0, hipEvent_t *e1)
 {
-    t.id = id;
-    t.e0 = t.e1 = nullptr;
     if (!ctx || !ctx->timing)
-        return;
-    t.e0 = take_event(ctx);
-    t.e1 = take_event(ctx);
-    if (!t.e0 || !t.e1)
-        return;
-    on = hipEventRecord(t.e0, st) == hipSuccess;
+        return false;
+    *e0 = take_event(ctx);
+    *e1 = take_event(ctx);
+    if (*e0 && *e1)
+        return true;
+    if (*e0)
+        ctx->event_pool.push_back(*e0);
+    if (*e1)
+        ctx->event_pool.push_back(*e1);
+    return false;
 }
 
-fae_ktimer::~fae_ktimer()
+void fae_timing_end(fae_ctx *ctx, hipEvent_t e0, hipEvent_t e1)
 {
-    if (!on)
-        return;
-    if (hipEventRecord(t.e1, st) == hipSuccess)
-        c->timed.push_back(t);
+    fae_timed_launch t;
+    t.id = ctx->cur_class;
+    t.e0 = e0;
+    t.e1 = e1;
+    ctx->timed.push_back(t);
 }
 
 static int32_t timing_collect(fae_ctx *ctx)
@@ -287,7 +288,7 @@ int32_t fae_sync_status(fae_ctx *ctx)
     uint32_t st = ctx->h_block[FAE_BLK_STATUS];
     if (st == 0)
         return FAE_OK;
-    hipLaunchKernelGGL(fae_clear_words_kernel, dim3(1), dim3(64), 0, ctx->stream, ctx->d_block, 1);
+    FAE_LAUNCH(ctx, fae_clear_words_kernel, dim3(1), dim3(64), 0, ctx->stream, ctx->d_block, 1);
     FAE_LAUNCH_CHECK(ctx);
     FAE_HIP(ctx, hipStreamSynchronize(ctx->stream));
     if (st & FAE_STATUS_EINTERNAL)

@@ -204,7 +204,7 @@ struct Estimator {
             a.cutoff[z] = H[z];
         {
             fae_ktimer kt(ctx, FAE_K_ESTIMATE);
-            hipLaunchKernelGGL(est_chunk_count_kernel, dim3((unsigned)plan.total), dim3(EST_THREADS), 0, ctx->stream, a);
+            FAE_LAUNCH(ctx, est_chunk_count_kernel, dim3((unsigned)plan.total), dim3(EST_THREADS), 0, ctx->stream, a);
             FAE_LAUNCH_CHECK(ctx);
         }
         FAE_HIP(ctx, hipMemcpyAsync(C.data(), a.C, (size_t)plan.total * sizeof(int32_t), hipMemcpyDeviceToHost,

@@ -152,11 +152,11 @@ template <typename V, int LPR> __global__ __launch_bounds__(256) void fwd_wave_k
 template <typename V, int LPR> static void fwd_launch(fae_ctx *ctx, const FwdArgs &a, int kind, int total_blocks)
 {
     if (kind == 2)
-        hipLaunchKernelGGL((fwd_onehot_kernel<V, LPR>), dim3(total_blocks), dim3(256), 0, ctx->stream, a);
+        FAE_LAUNCH(ctx, (fwd_onehot_kernel<V, LPR>), dim3(total_blocks), dim3(256), 0, ctx->stream, a);
     else if (kind == 1)
-        hipLaunchKernelGGL((fwd_wave_kernel<V, LPR>), dim3(total_blocks), dim3(256), 0, ctx->stream, a);
+        FAE_LAUNCH(ctx, (fwd_wave_kernel<V, LPR>), dim3(total_blocks), dim3(256), 0, ctx->stream, a);
     else
-        hipLaunchKernelGGL((fwd_group_kernel<V, LPR>), dim3(total_blocks), dim3(256), 0, ctx->stream, a);
+        FAE_LAUNCH(ctx, (fwd_group_kernel<V, LPR>), dim3(total_blocks), dim3(256), 0, ctx->stream, a);
 }
 
 template <typename V> static void fwd_dispatch(fae_ctx *ctx, const FwdArgs &a, int lpr, int kind, int total_blocks)

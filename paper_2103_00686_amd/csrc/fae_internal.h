@@ -2,6 +2,7 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 #include <stdio.h>
 #include <string.h>
@@ -122,22 +123,47 @@ struct fae_ctx {
     }
     // per-kernel timing
     bool timing = false;
+    int cur_class = FAE_K_OTHER;          // kernel class of the launches issued right now (set by fae_ktimer)
     std::vector<fae_timed_launch> timed;  // launches recorded since the last read
     std::vector<hipEvent_t> event_pool;   // events ready for reuse
     double t_total_ms[FAE_K_COUNT] = {0};
     int64_t t_launches[FAE_K_COUNT] = {0};
 };
 
-// Brackets the launches issued during its lifetime with two events (when timing is on).
+// Names the kernel class of the launches issued during its lifetime (for the per-kernel timing).
 struct fae_ktimer {
     fae_ctx *c;
-    fae_timed_launch t;
-    bool on;
-    hipStream_t st;
-    fae_ktimer(fae_ctx *ctx, int id);
-    fae_ktimer(fae_ctx *ctx, int id, hipStream_t stream);
-    ~fae_ktimer();
+    int prev;
+    fae_ktimer(fae_ctx *ctx, int id) : c(ctx), prev(ctx ? ctx->cur_class : 0)
+    {
+        if (c)
+            c->cur_class = id;
+    }
+    fae_ktimer(fae_ctx *ctx, int id, hipStream_t) : fae_ktimer(ctx, id) {}
+    ~fae_ktimer()
+    {
+        if (c)
+            c->cur_class = prev;
+    }
 };
+
+// With timing on: two events for one launch (false when timing is off or no event could be made);
+// fae_timing_end files them under the current kernel class.
+bool fae_timing_begin(fae_ctx *ctx, hipEvent_t *e0, hipEvent_t *e1);
+void fae_timing_end(fae_ctx *ctx, hipEvent_t e0, hipEvent_t e1);
+
+// Every kernel of the library is launched through this.  With timing on, the launch itself carries
+// the two events, which the device stamps at the kernel's own start and end: the figure does not
+// depend on whether the stream was idle, and holds nothing but the kernel.
+#define FAE_LAUNCH(ctx, kernel, grid, block, shmem, stream, ...)                                          \
+    do {                                                                                                  \
+        hipEvent_t e0_ = nullptr, e1_ = nullptr;                                                          \
+        if (fae_timing_begin((ctx), &e0_, &e1_)) {                                                        \
+            hipExtLaunchKernelGGL(kernel, grid, block, shmem, stream, e0_, e1_, 0, __VA_ARGS__);          \
+            fae_timing_end((ctx), e0_, e1_);                                                              \
+        } else                                                                                            \
+            hipLaunchKernelGGL(kernel, grid, block, shmem, stream, __VA_ARGS__);                          \
+    } while (0)
 
 int32_t fae_fail(fae_ctx *ctx, int32_t code, const char *fmt, ...);
 // fae_bwd.hip: device address of the built-in backward workspace on `device` (which is current)

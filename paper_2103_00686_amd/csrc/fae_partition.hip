@@ -263,24 +263,24 @@ extern "C" int32_t fae_partition_batch(fae_ctx *ctx, const fae_tables *tables, c
         return rc;
     if (blocks > 0) {
         fae_ktimer kt(ctx, FAE_K_PARTITION);
-        hipLaunchKernelGGL(part_mark_kernel, dim3((unsigned)blocks), dim3(256), 0, ctx->stream, a);
+        FAE_LAUNCH(ctx, part_mark_kernel, dim3((unsigned)blocks), dim3(256), 0, ctx->stream, a);
         FAE_LAUNCH_CHECK(ctx);
     }
     {
         fae_ktimer kt(ctx, FAE_K_PARTITION);
-        hipLaunchKernelGGL(part_count_kernel, dim3((unsigned)tiles, nt + 1), dim3(256), 0, ctx->stream, a);
+        FAE_LAUNCH(ctx, part_count_kernel, dim3((unsigned)tiles, nt + 1), dim3(256), 0, ctx->stream, a);
         FAE_LAUNCH_CHECK(ctx);
     }
     rc = fae_scan_i32(ctx, a.tile_sums, (int64_t)(nt + 1) * tiles);
     if (rc != FAE_OK)
         return rc;
     fae_ktimer kt(ctx, FAE_K_PARTITION);
-    hipLaunchKernelGGL(part_emit_kernel, dim3((unsigned)tiles), dim3(256), 0, ctx->stream, a);
+    FAE_LAUNCH(ctx, part_emit_kernel, dim3((unsigned)tiles), dim3(256), 0, ctx->stream, a);
     FAE_LAUNCH_CHECK(ctx);
-    hipLaunchKernelGGL(part_offsets_kernel, dim3((unsigned)tiles, nt), dim3(256), 0, ctx->stream, a);
+    FAE_LAUNCH(ctx, part_offsets_kernel, dim3((unsigned)tiles, nt), dim3(256), 0, ctx->stream, a);
     FAE_LAUNCH_CHECK(ctx);
     if (blocks > 0) {
-        hipLaunchKernelGGL(part_slots_kernel, dim3((unsigned)blocks), dim3(256), 0, ctx->stream, a);
+        FAE_LAUNCH(ctx, part_slots_kernel, dim3((unsigned)blocks), dim3(256), 0, ctx->stream, a);
         FAE_LAUNCH_CHECK(ctx);
     }
     rc = fae_readback(ctx, FAE_BLK_SCALARS, nt + 1);

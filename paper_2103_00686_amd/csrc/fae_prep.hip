@@ -169,9 +169,9 @@ extern "C" int32_t fae_profile(fae_ctx *ctx, const fae_tables *tables, const fae
         return fae_fail(ctx, FAE_EINVAL, "fae_profile: chunk too large for one launch");
     fae_ktimer kt(ctx, FAE_K_PROFILE);
     if (lds)
-        hipLaunchKernelGGL(prof_lds_kernel, dim3((unsigned)blocks), dim3(PROF_THREADS), 0, ctx->stream, a);
+        FAE_LAUNCH(ctx, prof_lds_kernel, dim3((unsigned)blocks), dim3(PROF_THREADS), 0, ctx->stream, a);
     else
-        hipLaunchKernelGGL(prof_atomic_kernel, dim3((unsigned)blocks), dim3(256), 0, ctx->stream, a);
+        FAE_LAUNCH(ctx, prof_atomic_kernel, dim3((unsigned)blocks), dim3(256), 0, ctx->stream, a);
     FAE_LAUNCH_CHECK(ctx);
     return FAE_OK;
 }
@@ -328,7 +328,7 @@ struct Window {
             return rc;
         if (blocks > 0) {
             fae_ktimer kt(ctx, FAE_K_BUILD);
-            hipLaunchKernelGGL(count_window_kernel, dim3((unsigned)blocks), dim3(256), 0, ctx->stream, a);
+            FAE_LAUNCH(ctx, count_window_kernel, dim3((unsigned)blocks), dim3(256), 0, ctx->stream, a);
             FAE_LAUNCH_CHECK(ctx);
         }
         host.resize((size_t)nt * CW_STRIDE);
@@ -724,7 +724,7 @@ extern "C" int32_t fae_build_hot_tables(fae_ctx *ctx, const fae_tables *tables, 
         return rc;
     if (tiles > 0) {
         fae_ktimer kt(ctx, FAE_K_BUILD);
-        hipLaunchKernelGGL(build_count_kernel, dim3((unsigned)tiles), dim3(256), 0, ctx->stream, a);
+        FAE_LAUNCH(ctx, build_count_kernel, dim3((unsigned)tiles), dim3(256), 0, ctx->stream, a);
         FAE_LAUNCH_CHECK(ctx);
     }
     rc = fae_scan_i32(ctx, a.tile_sums, tiles);
@@ -732,7 +732,7 @@ extern "C" int32_t fae_build_hot_tables(fae_ctx *ctx, const fae_tables *tables, 
         return rc;
     if (tiles > 0) {
         fae_ktimer kt(ctx, FAE_K_BUILD);
-        hipLaunchKernelGGL(build_scatter_kernel, dim3((unsigned)tiles), dim3(256), 0, ctx->stream, a);
+        FAE_LAUNCH(ctx, build_scatter_kernel, dim3((unsigned)tiles), dim3(256), 0, ctx->stream, a);
         FAE_LAUNCH_CHECK(ctx);
     }
     rc = fae_readback(ctx, FAE_BLK_SCALARS, nt);
@@ -774,9 +774,9 @@ extern "C" int32_t fae_build_hot_tables(fae_ctx *ctx, const fae_tables *tables, 
     if (blocks > 0) {
         fae_ktimer kt(ctx, FAE_K_BUILD);
         if (vec)
-            hipLaunchKernelGGL(gather_rows_kernel<float4>, dim3((unsigned)blocks), dim3(256), 0, ctx->stream, g);
+            FAE_LAUNCH(ctx, gather_rows_kernel<float4>, dim3((unsigned)blocks), dim3(256), 0, ctx->stream, g);
         else
-            hipLaunchKernelGGL(gather_rows_kernel<float>, dim3((unsigned)blocks), dim3(256), 0, ctx->stream, g);
+            FAE_LAUNCH(ctx, gather_rows_kernel<float>, dim3((unsigned)blocks), dim3(256), 0, ctx->stream, g);
         FAE_LAUNCH_CHECK(ctx);
     }
     FAE_HIP(ctx, hipStreamSynchronize(ctx->stream));

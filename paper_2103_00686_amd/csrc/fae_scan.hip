@@ -32,7 +32,7 @@ __global__ __launch_bounds__(1024) void fae_scan_kernel(int32_t *data, int64_t n
 int32_t fae_scan_i32(fae_ctx *ctx, int32_t *data, int64_t n)
 {
     fae_ktimer kt(ctx, FAE_K_OTHER);
-    hipLaunchKernelGGL(fae_scan_kernel, dim3(1), dim3(1024), 0, ctx->stream, data, n);
+    FAE_LAUNCH(ctx, fae_scan_kernel, dim3(1), dim3(1024), 0, ctx->stream, data, n);
     FAE_LAUNCH_CHECK(ctx);
     return FAE_OK;
 }
@@ -148,14 +148,14 @@ ProbeShape probe_shape(const fae_ctx *ctx, int64_t n, int best_unroll, int best_
     do {                                                                                                     \
         const dim3 g_((shape).grid), b_(256);                                                                \
         switch ((shape).unroll * 2 + (shape).nt) {                                                           \
-        case 2: hipLaunchKernelGGL((KERNEL<1, 0>), g_, b_, 0, ctx->stream, __VA_ARGS__); break;              \
-        case 3: hipLaunchKernelGGL((KERNEL<1, 1>), g_, b_, 0, ctx->stream, __VA_ARGS__); break;              \
-        case 4: hipLaunchKernelGGL((KERNEL<2, 0>), g_, b_, 0, ctx->stream, __VA_ARGS__); break;              \
-        case 5: hipLaunchKernelGGL((KERNEL<2, 1>), g_, b_, 0, ctx->stream, __VA_ARGS__); break;              \
-        case 8: hipLaunchKernelGGL((KERNEL<4, 0>), g_, b_, 0, ctx->stream, __VA_ARGS__); break;              \
-        case 9: hipLaunchKernelGGL((KERNEL<4, 1>), g_, b_, 0, ctx->stream, __VA_ARGS__); break;              \
-        case 16: hipLaunchKernelGGL((KERNEL<8, 0>), g_, b_, 0, ctx->stream, __VA_ARGS__); break;             \
-        default: hipLaunchKernelGGL((KERNEL<8, 1>), g_, b_, 0, ctx->stream, __VA_ARGS__); break;             \
+        case 2: FAE_LAUNCH(ctx, (KERNEL<1, 0>), g_, b_, 0, ctx->stream, __VA_ARGS__); break;              \
+        case 3: FAE_LAUNCH(ctx, (KERNEL<1, 1>), g_, b_, 0, ctx->stream, __VA_ARGS__); break;              \
+        case 4: FAE_LAUNCH(ctx, (KERNEL<2, 0>), g_, b_, 0, ctx->stream, __VA_ARGS__); break;              \
+        case 5: FAE_LAUNCH(ctx, (KERNEL<2, 1>), g_, b_, 0, ctx->stream, __VA_ARGS__); break;              \
+        case 8: FAE_LAUNCH(ctx, (KERNEL<4, 0>), g_, b_, 0, ctx->stream, __VA_ARGS__); break;              \
+        case 9: FAE_LAUNCH(ctx, (KERNEL<4, 1>), g_, b_, 0, ctx->stream, __VA_ARGS__); break;              \
+        case 16: FAE_LAUNCH(ctx, (KERNEL<8, 0>), g_, b_, 0, ctx->stream, __VA_ARGS__); break;             \
+        default: FAE_LAUNCH(ctx, (KERNEL<8, 1>), g_, b_, 0, ctx->stream, __VA_ARGS__); break;             \
         }                                                                                                    \
     } while (0)
 } // namespace
@@ -215,7 +215,7 @@ int32_t fae_fill_u32_on(fae_ctx *ctx, hipStream_t st, void *p, int64_t n_words, 
     if (blocks > 65536)
         blocks = 65536;
     fae_ktimer kt(ctx, FAE_K_FILL, st);
-    hipLaunchKernelGGL(fae_fill_kernel, dim3((unsigned)blocks), dim3(256), 0, st, (uint32_t *)p, n_words, v);
+    FAE_LAUNCH(ctx, fae_fill_kernel, dim3((unsigned)blocks), dim3(256), 0, st, (uint32_t *)p, n_words, v);
     FAE_LAUNCH_CHECK(ctx);
     return FAE_OK;
 }

@@ -115,9 +115,9 @@ extern "C" int32_t fae_sync_hot_rows(fae_ctx *ctx, const fae_tables *tables, con
     FAE_HIP(ctx, hipSetDevice(ctx->device));
     fae_ktimer kt(ctx, FAE_K_SYNC_ROWS);
     if (vec)
-        hipLaunchKernelGGL(sync_rows_kernel<float4>, dim3((unsigned)blocks), dim3(SYNC_THREADS), 0, ctx->stream, a);
+        FAE_LAUNCH(ctx, sync_rows_kernel<float4>, dim3((unsigned)blocks), dim3(SYNC_THREADS), 0, ctx->stream, a);
     else
-        hipLaunchKernelGGL(sync_rows_kernel<float>, dim3((unsigned)blocks), dim3(SYNC_THREADS), 0, ctx->stream, a);
+        FAE_LAUNCH(ctx, sync_rows_kernel<float>, dim3((unsigned)blocks), dim3(SYNC_THREADS), 0, ctx->stream, a);
     FAE_LAUNCH_CHECK(ctx);
     return FAE_OK;
 }
