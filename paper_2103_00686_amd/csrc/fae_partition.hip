@@ -16,7 +16,7 @@ struct PartArgs {
     int32_t *hoffsets[FAE_MAX_TABLES];
     int32_t n_rows[FAE_MAX_TABLES];
     int32_t n_lookups[FAE_MAX_TABLES];
-    int32_t blk_start[FAE_MAX_TABLES + 1]; // lookup-parallel kernels: blocks of 256 lookups
+    int32_t blk_start[FAE_MAX_TABLES + 1]; // lookup-parallel kernels: blocks of PT_BLOCK lookups
     int32_t n_tables;
     int32_t n_samples;
     int32_t n_tiles;      // sample tiles
@@ -29,23 +29,41 @@ struct PartArgs {
     uint32_t *scalars;    // device scalars: [0] = n_hot_samples, [1+z] = hot lookups of table z
 };
 
-// pass 1: mark samples with a cold (or invalid) access; one thread per lookup
+#define PT_LK 4                 // lookups per thread in the lookup-parallel kernels
+#define PT_BLOCK (256 * PT_LK)  // lookups per workgroup there
+
+// pass 1: mark samples with a cold (or invalid) access; PT_LK lookups per thread, a workgroup's
+// loads of one round next to each other.  All index loads go out first, then all remap gathers.
 __global__ __launch_bounds__(256) void part_mark_kernel(PartArgs a)
 {
     const int z = fae_find_table(a.blk_start, a.n_tables, blockIdx.x);
-    const int j = (blockIdx.x - a.blk_start[z]) * 256 + threadIdx.x;
-    if (j >= a.n_lookups[z])
-        return;
+    const int base = (blockIdx.x - a.blk_start[z]) * PT_BLOCK + threadIdx.x;
+    const int nl = a.n_lookups[z];
     const int32_t *off = a.offsets[z];
-    const int s = off ? fae_sample_of(off, a.n_samples, j) : j;
-    const int r = fae_load_row(a.idx[z], j, a.wide, a.n_rows[z]);
-    if (r < 0) {
-        fae_flag(a.status, FAE_STATUS_ERANGE);
-        a.cold[s] = 1u;
-        return;
+    const int32_t *remap = a.remap[z];
+    int r[PT_LK], s[PT_LK], m[PT_LK];
+#pragma unroll
+    for (int k = 0; k < PT_LK; ++k) {
+        const int j = base + k * 256;
+        r[k] = j < nl ? fae_load_row(a.idx[z], j, a.wide, a.n_rows[z]) : -2;
     }
-    if (a.remap[z][r] < 0)
-        a.cold[s] = 1u; // benign race: every writer stores the same value
+#pragma unroll
+    for (int k = 0; k < PT_LK; ++k) {
+        const int j = base + k * 256;
+        s[k] = (off && j < nl) ? fae_sample_of(off, a.n_samples, j) : j;
+    }
+#pragma unroll
+    for (int k = 0; k < PT_LK; ++k)
+        m[k] = r[k] >= 0 ? remap[r[k]] : -1;
+#pragma unroll
+    for (int k = 0; k < PT_LK; ++k) {
+        if (r[k] == -2)
+            continue;
+        if (r[k] < 0)
+            fae_flag(a.status, FAE_STATUS_ERANGE);
+        if (m[k] < 0)
+            a.cold[s[k]] = 1u; // benign race: every writer stores the same value
+    }
 }
 
 __device__ __forceinline__ int part_len(const PartArgs &a, int z, int s, bool *bad)
@@ -86,27 +104,30 @@ __global__ __launch_bounds__(256) void part_count_kernel(PartArgs a)
         a.tile_sums[row * a.n_tiles + tile] = total;
 }
 
-// pass 3 (after the scan of tile_sums): hot / cold sample lists and each sample's hot position
+// pass 3 (after the scan of tile_sums): hot / cold sample lists and each sample's hot position;
+// for the tables with one lookup per sample also the rebuilt offsets (hot sample h starts at h)
 __global__ __launch_bounds__(256) void part_emit_kernel(PartArgs a)
 {
     __shared__ int lds[256 / FAE_WAVE + 1];
     const int tile = blockIdx.x;
     int c = 0;
+    uint32_t cold[4];
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
         int s = tile * PT_TILE + threadIdx.x * 4 + k;
-        if (s < a.n_samples && !a.cold[s])
-            c += 1;
+        cold[k] = s < a.n_samples ? a.cold[s] : 1u;
+        c += cold[k] ? 0 : 1;
     }
     int total;
     int ex = fae_block_excl_scan<256>(c, lds, &total);
-    int run = a.tile_sums[tile] + ex; // row 0 starts the scanned array: its base is 0
+    const int run0 = a.tile_sums[tile] + ex; // row 0 starts the scanned array: its base is 0
+    int run = run0;
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
         int s = tile * PT_TILE + threadIdx.x * 4 + k;
         if (s >= a.n_samples)
             break;
-        if (!a.cold[s]) {
+        if (!cold[k]) {
             a.hot_samples[run] = s;
             a.hidx[s] = run;
             ++run;
@@ -115,6 +136,14 @@ __global__ __launch_bounds__(256) void part_emit_kernel(PartArgs a)
             a.hidx[s] = -1;
         }
     }
+    if (c > 0)
+        for (int z = 0; z < a.n_tables; ++z) {
+            if (a.offsets[z])
+                continue;
+            int32_t *hoff = a.hoffsets[z];
+            for (int h = run0; h < run; ++h)
+                hoff[h] = h;
+        }
 }
 
 // pass 3b: hoffsets_z[h] for every hot sample (needs hidx from pass 3, row 0)
@@ -123,30 +152,32 @@ __global__ __launch_bounds__(256) void part_offsets_kernel(PartArgs a)
     __shared__ int lds[256 / FAE_WAVE + 1];
     const int tile = blockIdx.x, z = blockIdx.y;
     const int row = z + 1;
-    int v[4];
-    int c = 0;
-    bool bad = false;
-#pragma unroll
-    for (int k = 0; k < 4; ++k) {
-        int s = tile * PT_TILE + threadIdx.x * 4 + k;
-        v[k] = 0;
-        if (s < a.n_samples && !a.cold[s])
-            v[k] = part_len(a, z, s, &bad);
-        c += v[k];
-    }
-    int total;
-    int ex = fae_block_excl_scan<256>(c, lds, &total);
     const int row_base = a.tile_sums[row * a.n_tiles];
-    int run = a.tile_sums[row * a.n_tiles + tile] - row_base + ex;
     int32_t *hoff = a.hoffsets[z];
+    if (a.offsets[z]) { // one lookup per sample otherwise: pass 3 has written those offsets
+        int v[4];
+        int c = 0;
+        bool bad = false;
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
-        int s = tile * PT_TILE + threadIdx.x * 4 + k;
-        if (s >= a.n_samples)
-            break;
-        if (!a.cold[s])
-            hoff[a.hidx[s]] = run;
-        run += v[k];
+        for (int k = 0; k < 4; ++k) {
+            int s = tile * PT_TILE + threadIdx.x * 4 + k;
+            v[k] = 0;
+            if (s < a.n_samples && !a.cold[s])
+                v[k] = part_len(a, z, s, &bad);
+            c += v[k];
+        }
+        int total;
+        int ex = fae_block_excl_scan<256>(c, lds, &total);
+        int run = a.tile_sums[row * a.n_tiles + tile] - row_base + ex;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            int s = tile * PT_TILE + threadIdx.x * 4 + k;
+            if (s >= a.n_samples)
+                break;
+            if (!a.cold[s])
+                hoff[a.hidx[s]] = run;
+            run += v[k];
+        }
     }
     if (tile == 0 && threadIdx.x == 0) {
         // totals: hot samples and hot lookups of this table; closing offset
@@ -159,25 +190,44 @@ __global__ __launch_bounds__(256) void part_offsets_kernel(PartArgs a)
     }
 }
 
-// pass 4: hot slots of the hot samples' lookups, one thread per input lookup
+// pass 4: hot slots of the hot samples' lookups, PT_LK input lookups per thread; loads of the same
+// kind go out together
 __global__ __launch_bounds__(256) void part_slots_kernel(PartArgs a)
 {
     const int z = fae_find_table(a.blk_start, a.n_tables, blockIdx.x);
-    const int j = (blockIdx.x - a.blk_start[z]) * 256 + threadIdx.x;
-    if (j >= a.n_lookups[z])
-        return;
+    const int base = (blockIdx.x - a.blk_start[z]) * PT_BLOCK + threadIdx.x;
+    const int nl = a.n_lookups[z];
     const int32_t *off = a.offsets[z];
-    const int s = off ? fae_sample_of(off, a.n_samples, j) : j;
-    if (a.cold[s])
-        return;
-    const int h = a.hidx[s];
-    const int within = off ? j - off[s] : 0;
-    const int dst = a.hoffsets[z][h] + within;
-    if (within < 0 || dst < 0 || dst >= a.n_lookups[z])
-        return; // malformed CSR (already flagged)
-    const int r = fae_load_row(a.idx[z], j, a.wide, a.n_rows[z]);
-    if (r >= 0) // always, for a hot sample: every index was validated in pass 1
-        a.slots[z][dst] = a.remap[z][r];
+    const int32_t *remap = a.remap[z];
+    const int32_t *hoff = a.hoffsets[z];
+    int s[PT_LK], h[PT_LK], r[PT_LK], dst[PT_LK], m[PT_LK];
+#pragma unroll
+    for (int k = 0; k < PT_LK; ++k) {
+        const int j = base + k * 256;
+        s[k] = j < nl ? (off ? fae_sample_of(off, a.n_samples, j) : j) : -1;
+    }
+#pragma unroll
+    for (int k = 0; k < PT_LK; ++k)
+        h[k] = s[k] >= 0 ? a.hidx[s[k]] : -1; // -1 for a cold sample
+#pragma unroll
+    for (int k = 0; k < PT_LK; ++k) {
+        const int j = base + k * 256;
+        r[k] = h[k] >= 0 ? fae_load_row(a.idx[z], j, a.wide, a.n_rows[z]) : -1;
+        dst[k] = -1;
+        if (h[k] >= 0) {
+            const int within = off ? j - off[s[k]] : 0;
+            const int d = (off ? hoff[h[k]] : h[k]) + within;
+            if (within >= 0 && d >= 0 && d < nl) // else: malformed CSR (already flagged)
+                dst[k] = d;
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < PT_LK; ++k)
+        m[k] = (r[k] >= 0 && dst[k] >= 0) ? remap[r[k]] : -1; // r >= 0 always, for a hot sample: pass 1 validated every index
+#pragma unroll
+    for (int k = 0; k < PT_LK; ++k)
+        if (r[k] >= 0 && dst[k] >= 0)
+            a.slots[z][dst[k]] = m[k];
 }
 
 static int64_t part_tiles(int64_t S) { return (S + PT_TILE - 1) / PT_TILE; }
@@ -245,7 +295,7 @@ extern "C" int32_t fae_partition_batch(fae_ctx *ctx, const fae_tables *tables, c
         a.n_rows[z] = (int32_t)tables->h_rows[z];
         a.n_lookups[z] = (int32_t)in->h_n_lookups[z];
         a.blk_start[z] = (int32_t)blocks;
-        blocks += (in->h_n_lookups[z] + 255) / 256;
+        blocks += (in->h_n_lookups[z] + PT_BLOCK - 1) / PT_BLOCK;
     }
     a.blk_start[nt] = (int32_t)blocks;
     if (blocks >= 2147483647LL)
