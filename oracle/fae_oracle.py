@@ -1,9 +1,17 @@
 """ctypes/numpy front end of the CPU oracle (``fae_oracle.c``).
 
 TEST INFRASTRUCTURE ONLY: imported by ``tests/``, ``__graft_entry__.smoke()`` and
-the ``cpu_baseline`` leg of ``bench.py``; never by the product package.  It
-marshals numpy arrays into the C functions and loops over tables; all arithmetic
-lives in the C file.
+``bench.py`` (its ``cpu_baseline`` legs and its check of steps 1 and 3 outside the timed
+region); never by the product package.  Most of it marshals numpy arrays into the C
+functions and loops over tables.  Three pieces of the method's arithmetic are written
+here, in plain Python, because they are a few lines on scalars:
+  ``t_quantile``            the Student-t quantile of Eq. 4, from the library routine
+                            (pinned against printed t-table values);
+  ``sampled_budget_cutoff`` the threshold scan of the Statistical Optimizer on the sampled
+                            logger (Sec. 4.1.2): c = 0, 1, 2, ... until the estimated bytes fit;
+  ``shuffle_scheduler``     the rate rule of Eq. 5.
+``estimate_hot_rows`` scales Eq. 3 and Eq. 4 from a chunk to the table (times N).
+Everything else that computes lives in the C file.
 """
 from __future__ import annotations
 
