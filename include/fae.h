@@ -118,9 +118,12 @@ int32_t fae_sync(fae_ctx *ctx);
 int32_t fae_set_option(fae_ctx *ctx, const char *name, int64_t value);
 
 /* ---- per-kernel timing (measurement aid; off by default) ---------------------- */
-/* When enabled, every kernel launch of the listed classes is bracketed by HIP events
- * on the context's stream.  fae_timing_read synchronises and returns, for one kernel
- * class, the summed duration and the number of launches since the last reset. */
+/* When enabled, every kernel launch of the library carries two HIP events that the
+ * device stamps at the kernel's own start and end, so a figure holds the kernel and
+ * nothing else (no host launch latency, whether or not the stream was idle).
+ * fae_timing_read synchronises and returns, for one kernel class, the summed duration
+ * and the number of launches since the last reset.  Keep it off while a stream of the
+ * context is being captured into a graph: such launches cannot be captured. */
 #define FAE_K_FWD 0          /* pooled forward                                  */
 #define FAE_K_BWD_KEYS 1     /* (slot, sample) pairs                            */
 #define FAE_K_SORT_HIST 2    /* radix pass: per-tile digit histogram            */
