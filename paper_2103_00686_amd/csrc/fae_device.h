@@ -11,6 +11,17 @@
 // 16-byte (or scalar) column slices
 // ---------------------------------------------------------------------------------
 template <typename V> struct vec_ops;
+// s += v with the rounding error of the addition carried in c (compensated summation): the error
+// of a long sum then stays at a few units of the last place whatever its length, also where one
+// row is added over and over (a popular row in a long bag), which otherwise drifts one way.
+__device__ __forceinline__ void fae_add_comp(float &s, float &c, float v)
+{
+    const float y = v - c;
+    const float t = s + y;
+    c = (t - s) - y;
+    s = t;
+}
+
 template <> struct vec_ops<float4> {
     static __device__ __forceinline__ float4 zero() { return make_float4(0.f, 0.f, 0.f, 0.f); }
     static __device__ __forceinline__ void add(float4 &a, const float4 &b)
@@ -27,6 +38,13 @@ template <> struct vec_ops<float4> {
         a.z *= f;
         a.w *= f;
     }
+    static __device__ __forceinline__ void add_comp(float4 &s, float4 &c, const float4 &v)
+    {
+        fae_add_comp(s.x, c.x, v.x);
+        fae_add_comp(s.y, c.y, v.y);
+        fae_add_comp(s.z, c.z, v.z);
+        fae_add_comp(s.w, c.w, v.w);
+    }
     static __device__ __forceinline__ float4 shfl_xor(const float4 &a, int m)
     {
         return make_float4(__shfl_xor(a.x, m, FAE_WAVE), __shfl_xor(a.y, m, FAE_WAVE),
@@ -37,6 +55,7 @@ template <> struct vec_ops<float> {
     static __device__ __forceinline__ float zero() { return 0.f; }
     static __device__ __forceinline__ void add(float &a, const float &b) { a += b; }
     static __device__ __forceinline__ void scale(float &a, float f) { a *= f; }
+    static __device__ __forceinline__ void add_comp(float &s, float &c, const float &v) { fae_add_comp(s, c, v); }
     static __device__ __forceinline__ float shfl_xor(const float &a, int m) { return __shfl_xor(a, m, FAE_WAVE); }
 };
 

@@ -39,6 +39,46 @@ __device__ __forceinline__ V fwd_load(const V *W, int slot, int n_hot, int ncols
     return W[(int64_t)slot * ncols + c];
 }
 
+// Sum of the rows of lookups j0, j0 + step, ... below end (column slice c), four loads in flight.
+// Up to FWD_PLAIN_MAX terms are added one after the other (worst case FWD_PLAIN_MAX * 2^-24 of
+// the sum of their magnitudes, inside the 1e-5 the result is held to); longer sums carry the
+// rounding error along (COMP), so that a bag of thousands of lookups stays as accurate as a short
+// one, also when it adds one popular row over and over, which otherwise drifts one way.
+#define FWD_PLAIN_MAX 128
+template <typename V, bool COMP>
+__device__ __forceinline__ V fwd_sum(const V *W, const int32_t *slots, int j0, int end, int step, int n_hot, int ncols, int c,
+                                     uint32_t *status)
+{
+    V acc = vec_ops<V>::zero(), lost = vec_ops<V>::zero();
+    int j = j0;
+    for (; j + 3 * step < end; j += 4 * step) {
+        const int s0 = slots[j], s1 = slots[j + step], s2 = slots[j + 2 * step], s3 = slots[j + 3 * step];
+        const V v0 = fwd_load(W, s0, n_hot, ncols, c, status);
+        const V v1 = fwd_load(W, s1, n_hot, ncols, c, status);
+        const V v2 = fwd_load(W, s2, n_hot, ncols, c, status);
+        const V v3 = fwd_load(W, s3, n_hot, ncols, c, status);
+        if (COMP) {
+            vec_ops<V>::add_comp(acc, lost, v0);
+            vec_ops<V>::add_comp(acc, lost, v1);
+            vec_ops<V>::add_comp(acc, lost, v2);
+            vec_ops<V>::add_comp(acc, lost, v3);
+        } else {
+            vec_ops<V>::add(acc, v0);
+            vec_ops<V>::add(acc, v1);
+            vec_ops<V>::add(acc, v2);
+            vec_ops<V>::add(acc, v3);
+        }
+    }
+    for (; j < end; j += step) {
+        const V v = fwd_load(W, slots[j], n_hot, ncols, c, status);
+        if (COMP)
+            vec_ops<V>::add_comp(acc, lost, v);
+        else
+            vec_ops<V>::add(acc, v);
+    }
+    return acc;
+}
+
 template <typename V, int LPR> __global__ __launch_bounds__(256) void fwd_group_kernel(FwdArgs a)
 {
     constexpr int GPB = 256 / LPR;
@@ -61,26 +101,12 @@ template <typename V, int LPR> __global__ __launch_bounds__(256) void fwd_group_
     const int n_hot = a.n_hot[z];
     V *o = (V *)(a.out + s * a.out_stride + (int64_t)z * a.dim);
     for (int c = l; c < ncols; c += LPR) {
-        V acc = vec_ops<V>::zero();
-        int j = beg;
-        for (; j + 4 <= end; j += 4) {
-            int s0 = slots[j], s1 = slots[j + 1], s2 = slots[j + 2], s3 = slots[j + 3];
-            V v0 = fwd_load(W, s0, n_hot, ncols, c, a.status);
-            V v1 = fwd_load(W, s1, n_hot, ncols, c, a.status);
-            V v2 = fwd_load(W, s2, n_hot, ncols, c, a.status);
-            V v3 = fwd_load(W, s3, n_hot, ncols, c, a.status);
-            vec_ops<V>::add(acc, v0);
-            vec_ops<V>::add(acc, v1);
-            vec_ops<V>::add(acc, v2);
-            vec_ops<V>::add(acc, v3);
-        }
-        for (; j < end; ++j) {
-            V v = fwd_load(W, slots[j], n_hot, ncols, c, a.status);
-            vec_ops<V>::add(acc, v);
-        }
+        const V acc = end - beg > FWD_PLAIN_MAX ? fwd_sum<V, true>(W, slots, beg, end, 1, n_hot, ncols, c, a.status)
+                                                : fwd_sum<V, false>(W, slots, beg, end, 1, n_hot, ncols, c, a.status);
+        V res = acc;
         if (a.mean && end - beg > 1)
-            vec_ops<V>::scale(acc, 1.0f / (float)(end - beg));
-        o[c] = acc;
+            vec_ops<V>::scale(res, 1.0f / (float)(end - beg));
+        o[c] = res;
     }
 }
 
@@ -120,24 +146,9 @@ template <typename V, int LPR> __global__ __launch_bounds__(256) void fwd_wave_k
     for (int c0 = 0; c0 < ncols; c0 += LPR) {
         const int c = c0 + l;
         V acc = vec_ops<V>::zero();
-        if (c < ncols) {
-            int j = beg + g;
-            for (; j + 3 * G < end; j += 4 * G) {
-                int s0 = slots[j], s1 = slots[j + G], s2 = slots[j + 2 * G], s3 = slots[j + 3 * G];
-                V v0 = fwd_load(W, s0, n_hot, ncols, c, a.status);
-                V v1 = fwd_load(W, s1, n_hot, ncols, c, a.status);
-                V v2 = fwd_load(W, s2, n_hot, ncols, c, a.status);
-                V v3 = fwd_load(W, s3, n_hot, ncols, c, a.status);
-                vec_ops<V>::add(acc, v0);
-                vec_ops<V>::add(acc, v1);
-                vec_ops<V>::add(acc, v2);
-                vec_ops<V>::add(acc, v3);
-            }
-            for (; j < end; j += G) {
-                V v = fwd_load(W, slots[j], n_hot, ncols, c, a.status);
-                vec_ops<V>::add(acc, v);
-            }
-        }
+        if (c < ncols) // every group sums every G-th lookup of the bag (the bag's length is the same for the whole wave)
+            acc = end - beg > FWD_PLAIN_MAX * G ? fwd_sum<V, true>(W, slots, beg + g, end, G, n_hot, ncols, c, a.status)
+                                                : fwd_sum<V, false>(W, slots, beg + g, end, G, n_hot, ncols, c, a.status);
         // combine the lane groups (all 64 lanes take part in the shuffles)
 #pragma unroll
         for (int m = LPR; m < FAE_WAVE; m <<= 1)

@@ -324,6 +324,47 @@ def test_table_count_and_sort_tier_limits(dev, nt, S_, fused):
         T.assert_close_sum(hp.hotW[z].cpu().numpy()[uniq[z]], Wref[z][uniq[z]], mg[z], f"table {z}")
 
 
+@pytest.mark.parametrize("fwd_variant", [1, 2])
+def test_long_bags_that_repeat_one_row(dev, fwd_variant):
+    """A bag of thousands of lookups most of which hit one popular row: added one after the other
+    in fp32 the rounding errors all point the same way and the sum drifts past 1e-5 of the terms'
+    magnitudes; the forward carries the rounding error along in long sums.  Both lane mappings
+    (group per bag, wave per bag), a vector and a scalar row width, then the backward on the same
+    batch (its runs hold the same gradient row thousands of times)."""
+    rng = np.random.default_rng(99 + fwd_variant)
+    for dim in (16, 6):
+        n_hot, S_, lr = [700, 5], 96, 0.05
+        Wref = [(rng.random((n, dim), dtype=np.float32) - 0.5) for n in n_hot]
+        slots, offs = [], []
+        for z, n in enumerate(n_hot):
+            lens = rng.integers(0, 6, S_)
+            lens[7], lens[40], lens[95] = 2231, 5000, 129
+            o = np.zeros(S_ + 1, dtype=np.int32)
+            o[1:] = np.cumsum(lens)
+            s_ = rng.integers(0, n, int(o[-1])).astype(np.int32)
+            for b, frac in ((7, 0.7), (40, 1.0), (95, 0.5)):          # most of a long bag is one row
+                seg = s_[o[b]:o[b + 1]]
+                seg[rng.random(seg.size) < frac] = int(rng.integers(0, n))
+            slots.append(s_)
+            offs.append(o)
+        hp = HotPath(n_hot, dim, 0)
+        B.fae_set_option(hp.ctx, "fwd_variant", fwd_variant)
+        hp.n_hot = n_hot
+        hp.hotW = [torch.from_numpy(x.copy()).to(dev) for x in Wref]
+        hb = HotBatch(S_, [torch.from_numpy(x).to(dev) for x in slots], [torch.from_numpy(o).to(dev) for o in offs],
+                      [x.size for x in slots])
+        out = hp.forward(hb).cpu().numpy()
+        ref, mag = O.embbag_fwd(Wref, S_, slots, offs, want_mag=True)
+        T.assert_close_sum(out, ref, mag, f"forward, dim {dim}")
+        gout = torch.from_numpy(rng.standard_normal((S_, 2, dim)).astype(np.float32))
+        dbg = hp.backward_sgd(hb, gout.to(dev), lr, debug=True)
+        hp.sync()
+        uniq, runlen, mg = O.embbag_bwd_sgd(Wref, S_, slots, offs, gout.numpy(), lr, want_mag=True)
+        for z in range(2):
+            assert np.array_equal(dbg[0][z].cpu().numpy(), uniq[z]) and np.array_equal(dbg[1][z].cpu().numpy(), runlen[z])
+            T.assert_close_sum(hp.hotW[z].cpu().numpy()[uniq[z]], Wref[z][uniq[z]], mg[z], f"table {z}, dim {dim}")
+
+
 def test_integer_valued_case_is_bit_exact(dev):
     """Integer weights/gradients and lr a power of two: every summation order is exact, so
     forward and update must match the oracle bit for bit."""
